@@ -1,0 +1,211 @@
+/*
+ * cube3d — per-rank hot path of the 3-D model-parallel linear layer
+ * (Bian, Xu, Wang, You: "Maximizing Parallelism in Distributed Training for
+ * Huge Neural Networks"), for AMD MI355X (gfx950).
+ *
+ * The layer computes Y = X W on a q x q x q processor cube.  Processor
+ * (i, j, l) multiplies one [M/q, K/q] block of X by one [K/q, N/q] block of W
+ * (Section 2.3; Algorithm 1), and in the backward pass forms dX = dY W^T and
+ * dW = X^T dY block products (Section 3.1.2, first differentiation formula;
+ * Algorithm 2).  Before the products the blocks are all-gathered along one
+ * cube direction from evenly spread shards, after them the partial results are
+ * reduce-scattered along another (Section 3.1.1).  On one GPU the cube is
+ * "virtual": the buffers of all q^3 processors live in one device's memory and
+ * the collectives are copy / reduction kernels.
+ *
+ * Notation (repository <-> paper): X [M,K] = A (M,N); W [K,N] = B (N,K);
+ * Y [M,N] = C (M,K); q = p.  Sizes derived by the library:
+ *     Mb = M/q, Kb = K/q, Nb = N/q   (block sizes)
+ *     Ms = M/q^2, Ns = N/q^2         (shard sizes)
+ * All matrices are row-major and densely packed (leading dimension = number of
+ * columns).
+ *
+ * Directions.  Processor (i, j, l) has index i along x, j along y, l along z.
+ * Weights always move along x.  `in_axis` names the direction in which the
+ * input X is gathered; the output is reduce-scattered along the other one of
+ * {y, z}.  in_axis = CUBE3D_AXIS_Y is the layout printed in Section 3.1.1;
+ * in_axis = CUBE3D_AXIS_Z is the exchanged assignment used by a layer that
+ * consumes the previous layer's output in place (Section 3.1.1, last
+ * paragraph; Section 3.2).  With a = index along the input direction and
+ * b = index along the output direction ((a,b) = (j,l) or (l,j)):
+ *     X shard  = X[i*Mb + a*Ms : +Ms, b*Kb : +Kb]          [Ms, Kb]
+ *     W shard  = W[b*Kb : +Kb,       a*Nb + i*Ns : +Ns]    [Kb, Ns]
+ *     Y shard  = Y[i*Mb + b*Ms : +Ms, a*Nb : +Nb]          [Ms, Nb]
+ *     X block  = X[i*Mb : +Mb, b*Kb : +Kb]                 [Mb, Kb]
+ *     W block  = W[b*Kb : +Kb, a*Nb : +Nb]                 [Kb, Nb]
+ *     Y block  = Y[i*Mb : +Mb, a*Nb : +Nb]                 [Mb, Nb]
+ * dY is stored like Y, dX like X, dW like W.
+ *
+ * Virtual-cube buffers.  A cube buffer holds one packed row-major block per
+ * processor, q^3 blocks back to back, processor (i, j, l) at block index
+ * r = (i*q + j)*q + l.  (The paper fixes no linear order; this is ours.)
+ *
+ * Ownership and execution.  Every data pointer is DEVICE memory owned by the
+ * caller; `desc` is HOST memory read during the call only.  The library
+ * allocates nothing, keeps no state between calls, never synchronises the
+ * device and enqueues work only on the caller's stream (`stream` is a
+ * hipStream_t passed as void*; NULL = the default stream).  Outputs are fully
+ * overwritten.  Inputs and outputs must not overlap.  Data pointers must be
+ * 16-byte aligned.
+ *
+ * Errors.  Every call returns a cube3d_status; 0 is success.  All argument
+ * checks happen on the host before anything is enqueued, so a failed call has
+ * no effect on the device.
+ */
+#ifndef CUBE3D_H
+#define CUBE3D_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CUBE3D_VERSION 100
+
+typedef enum cube3d_status {
+    CUBE3D_OK = 0,
+    CUBE3D_EINVAL = -1,     /* null pointer, q < 1, bad enum, bad rank coordinates */
+    CUBE3D_ESHAPE = -2,     /* q^2 must divide M and N, q must divide K; sizes must be positive */
+    CUBE3D_EDTYPE = -3,     /* unsupported in/out dtype combination */
+    CUBE3D_EWORKSPACE = -4, /* workspace smaller than cube3d_workspace_bytes() */
+    CUBE3D_ELAUNCH = -5,    /* the HIP runtime refused a launch */
+    CUBE3D_ENOTIMPL = -6
+} cube3d_status;
+
+typedef enum cube3d_dtype {
+    CUBE3D_F32 = 0,
+    CUBE3D_BF16 = 1,
+    CUBE3D_FP8_E4M3 = 2     /* OCP e4m3 "fn": bias 7, no infinities, max finite 448 */
+} cube3d_dtype;
+
+typedef enum cube3d_axis {
+    CUBE3D_AXIS_X = 0,      /* over i */
+    CUBE3D_AXIS_Y = 1,      /* over j */
+    CUBE3D_AXIS_Z = 2       /* over l */
+} cube3d_axis;
+
+typedef enum cube3d_operand {
+    CUBE3D_OPERAND_X = 0,
+    CUBE3D_OPERAND_W = 1,
+    CUBE3D_OPERAND_DY = 2,
+    CUBE3D_OPERAND_Y = 3,
+    CUBE3D_OPERAND_DX = 4,
+    CUBE3D_OPERAND_DW = 5
+} cube3d_operand;
+
+typedef enum cube3d_op {
+    CUBE3D_OP_FWD = 0,
+    CUBE3D_OP_BWD_DX = 1,
+    CUBE3D_OP_BWD_DW = 2
+} cube3d_op;
+
+/*
+ * Problem descriptor (host memory).  M, K, N are the GLOBAL sizes of the layer.
+ *   in_dtype     storage type of X, W and dY (shards and gathered blocks)
+ *   out_dtype    storage type of the per-processor partial products written by
+ *                the three product calls and read by the reduce-scatter:
+ *                CUBE3D_F32 or CUBE3D_BF16.  Products always accumulate in fp32.
+ *   shard_dtype  storage type of reduce-scatter results (Y, dX, dW shards):
+ *                CUBE3D_F32 or CUBE3D_BF16
+ *   scale_x/w/dy per-tensor dequantisation scales (real value = code * scale),
+ *                used when in_dtype is CUBE3D_FP8_E4M3 and ignored otherwise;
+ *                a product multiplies its fp32 accumulator by the two scales
+ *                of its operands before the store.
+ * The paper states no precision; these follow the benchmark configurations.
+ */
+typedef struct cube3d_desc {
+    int32_t q;
+    int32_t in_axis;        /* CUBE3D_AXIS_Y or CUBE3D_AXIS_Z */
+    int64_t M, K, N;
+    int32_t in_dtype;
+    int32_t out_dtype;
+    int32_t shard_dtype;
+    float scale_x, scale_w, scale_dy;
+} cube3d_desc;
+
+/*
+ * Rank coordinates for the three product calls: either a processor of the
+ * cube, 0 <= i, j, l < q, in which case the data pointers address that one
+ * processor's packed blocks; or i = j = l = -1, meaning ALL q^3 processors in
+ * one batched launch, in which case every data pointer addresses a cube
+ * buffer (block r of each buffer belongs to processor r).  The coordinates do
+ * not change the arithmetic of a single-processor call.
+ *
+ * `workspace` is device scratch of at least cube3d_workspace_bytes() bytes
+ * (may be NULL when that is 0).  Its contents are undefined afterwards.
+ */
+
+/* Algorithm 1, step 3:  P = X_block * W_block.
+ *   X_block [Mb, Kb] in_dtype, W_block [Kb, Nb] in_dtype  ->  P [Mb, Nb] out_dtype */
+int cube3d_linear_fwd(const cube3d_desc *desc, int i, int j, int l,
+                      const void *X_block, const void *W_block, void *P,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* Algorithm 2, line 1 (the local product of Algorithm 3):  Q = dY_block * W_block^T.
+ *   dY_block [Mb, Nb], W_block [Kb, Nb]  ->  Q [Mb, Kb] out_dtype */
+int cube3d_linear_bwd_dx(const cube3d_desc *desc, int i, int j, int l,
+                         const void *dY_block, const void *W_block, void *Q,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Algorithm 2, line 2 (the local product of Algorithm 5):  R = X_block^T * dY_block.
+ *   X_block [Mb, Kb], dY_block [Mb, Nb]  ->  R [Kb, Nb] out_dtype */
+int cube3d_linear_bwd_dw(const cube3d_desc *desc, int i, int j, int l,
+                         const void *X_block, const void *dY_block, void *R,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch needed by a product call.  op is a cube3d_op; batched != 0 asks for
+ * the all-processors launch.  Returns 0 for an invalid descriptor. */
+size_t cube3d_workspace_bytes(const cube3d_desc *desc, int op, int batched);
+
+/*
+ * All-gather over the whole virtual cube (Section 3.1.1; Algorithm 1 steps 1-2;
+ * for dY, the first step of the products Algorithm 2 invokes).
+ *   which = X  : axis must be desc->in_axis.  shards: cube buffer of [Ms, Kb];
+ *                gathered: cube buffer of [Mb, Kb], row panel a' taken from the
+ *                processor with input index a'.
+ *   which = W  : axis must be CUBE3D_AXIS_X.  shards [Kb, Ns] -> gathered
+ *                [Kb, Nb], column panel i' taken from the processor with x index i'.
+ *   which = DY : axis must be the output direction.  shards [Ms, Nb] ->
+ *                gathered [Mb, Nb], row panel b' from the processor with output index b'.
+ * Elements are in_dtype and are copied bit for bit.
+ */
+int virtual_cube_gather(const cube3d_desc *desc, int which, int axis,
+                        const void *shards, void *gathered, void *stream);
+
+/*
+ * Reduce-scatter over the whole virtual cube (Section 3.1.1; Algorithm 1 step 4;
+ * third directions of Algorithm 2).  Partials are out_dtype, sums are formed in
+ * fp32 in ascending order of the index along `axis`, and rounded once to
+ * shard_dtype (nearest even).
+ *   which = Y  : axis = output direction.  partials [Mb, Nb] -> shards [Ms, Nb];
+ *                the processor with output index b keeps row panel b.
+ *   which = DX : axis = desc->in_axis.  partials [Mb, Kb] -> shards [Ms, Kb];
+ *                the processor with input index a keeps row panel a.
+ *   which = DW : axis = CUBE3D_AXIS_X.  partials [Kb, Nb] -> shards [Kb, Ns];
+ *                processor i keeps column panel i.
+ */
+int virtual_cube_reduce_scatter(const cube3d_desc *desc, int which, int axis,
+                                const void *partials, void *shards, void *stream);
+
+/*
+ * The load-balanced storage itself (Section 3.1.1): spread a full row-major
+ * matrix over the cube, or collect it back.
+ *   which = X / DX : full [M, K] <-> cube buffer of [Ms, Kb]
+ *   which = W / DW : full [K, N] <-> cube buffer of [Kb, Ns]
+ *   which = Y / DY : full [M, N] <-> cube buffer of [Ms, Nb]
+ * X, W, DY are in_dtype; Y, DX, DW are shard_dtype.  Bit-for-bit copies.
+ */
+int virtual_cube_scatter(const cube3d_desc *desc, int which,
+                         const void *full, void *shards, void *stream);
+int virtual_cube_assemble(const cube3d_desc *desc, int which,
+                          const void *shards, void *full, void *stream);
+
+const char *cube3d_status_string(int status);
+int cube3d_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CUBE3D_H */

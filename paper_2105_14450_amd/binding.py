@@ -1,0 +1,166 @@
+"""Thin ctypes binding over ``libcube3d.so`` (see ``include/cube3d.h``).
+
+Argument marshalling only: every function takes torch CUDA tensors (device
+memory) and forwards raw pointers plus the current HIP stream to the C entry
+point of the same name.  There is no fallback: if the library is missing the
+import of a function raises, and a non-zero status raises ``Cube3DError``.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcube3d.so")
+
+OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH, ENOTIMPL = 0, -1, -2, -3, -4, -5, -6
+F32, BF16, FP8_E4M3 = 0, 1, 2
+AXIS_X, AXIS_Y, AXIS_Z = 0, 1, 2
+OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW = range(6)
+OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
+ALL_RANKS = (-1, -1, -1)
+
+DTYPE_CODES = {"f32": F32, "bf16": BF16, "fp8_e4m3": FP8_E4M3}
+ELEM_SIZE = {F32: 4, BF16: 2, FP8_E4M3: 1}
+
+
+class Desc(ctypes.Structure):
+    """Mirror of ``cube3d_desc``."""
+    _fields_ = [("q", ctypes.c_int32), ("in_axis", ctypes.c_int32),
+                ("M", ctypes.c_int64), ("K", ctypes.c_int64), ("N", ctypes.c_int64),
+                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("shard_dtype", ctypes.c_int32),
+                ("scale_x", ctypes.c_float), ("scale_w", ctypes.c_float),
+                ("scale_dy", ctypes.c_float)]
+
+
+def make_desc(q, M, K, N, in_dtype=BF16, out_dtype=F32, shard_dtype=None, in_axis=AXIS_Y,
+              scale_x=1.0, scale_w=1.0, scale_dy=1.0) -> Desc:
+    if shard_dtype is None:
+        shard_dtype = F32 if in_dtype == F32 else BF16
+    return Desc(q, in_axis, M, K, N, in_dtype, out_dtype, shard_dtype, scale_x, scale_w, scale_dy)
+
+
+class Cube3DError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def load():
+    """Load the library (after torch, so both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libcube3d.so is not built: run `python -m paper_2105_14450_amd.build`")
+    try:
+        import torch  # noqa: F401  (loads the HIP runtime the tensors come from)
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    dp = ctypes.POINTER(Desc)
+    for name in ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw"):
+        f = getattr(lib, name)
+        f.argtypes = [dp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        f.restype = ci
+    lib.cube3d_workspace_bytes.argtypes = [dp, ci, ci]
+    lib.cube3d_workspace_bytes.restype = sz
+    for name in ("virtual_cube_gather", "virtual_cube_reduce_scatter"):
+        f = getattr(lib, name)
+        f.argtypes = [dp, ci, ci, vp, vp, vp]
+        f.restype = ci
+    for name in ("virtual_cube_scatter", "virtual_cube_assemble"):
+        f = getattr(lib, name)
+        f.argtypes = [dp, ci, vp, vp, vp]
+        f.restype = ci
+    lib.cube3d_status_string.argtypes = [ci]
+    lib.cube3d_status_string.restype = ctypes.c_char_p
+    lib.cube3d_version.restype = ci
+    _lib = lib
+    return lib
+
+
+EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", "cube3d_workspace_bytes",
+           "virtual_cube_gather", "virtual_cube_reduce_scatter", "virtual_cube_scatter",
+           "virtual_cube_assemble", "cube3d_status_string", "cube3d_version")
+
+
+def status_string(status: int) -> str:
+    return load().cube3d_status_string(int(status)).decode()
+
+
+def cube3d_version() -> int:
+    return int(load().cube3d_version())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise Cube3DError(rc, where)
+
+
+def cube3d_workspace_bytes(desc: Desc, op: int, batched: bool) -> int:
+    return int(load().cube3d_workspace_bytes(ctypes.byref(desc), op, 1 if batched else 0))
+
+
+def _product(name, desc, rank, a, b, out, workspace, stream):
+    i, j, l = rank
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = getattr(load(), name)(ctypes.byref(desc), i, j, l, _ptr(a), _ptr(b), _ptr(out),
+                               _ptr(workspace), ws_bytes, _stream(stream))
+    _check(rc, name)
+    return out
+
+
+def cube3d_linear_fwd(desc, rank, X_block, W_block, P, workspace=None, stream=None):
+    return _product("cube3d_linear_fwd", desc, rank, X_block, W_block, P, workspace, stream)
+
+
+def cube3d_linear_bwd_dx(desc, rank, dY_block, W_block, Q, workspace=None, stream=None):
+    return _product("cube3d_linear_bwd_dx", desc, rank, dY_block, W_block, Q, workspace, stream)
+
+
+def cube3d_linear_bwd_dw(desc, rank, X_block, dY_block, R, workspace=None, stream=None):
+    return _product("cube3d_linear_bwd_dw", desc, rank, X_block, dY_block, R, workspace, stream)
+
+
+def virtual_cube_gather(desc, which, axis, shards, gathered, stream=None):
+    _check(load().virtual_cube_gather(ctypes.byref(desc), which, axis, _ptr(shards), _ptr(gathered),
+                                      _stream(stream)), "virtual_cube_gather")
+    return gathered
+
+
+def virtual_cube_reduce_scatter(desc, which, axis, partials, shards, stream=None):
+    _check(load().virtual_cube_reduce_scatter(ctypes.byref(desc), which, axis, _ptr(partials), _ptr(shards),
+                                              _stream(stream)), "virtual_cube_reduce_scatter")
+    return shards
+
+
+def virtual_cube_scatter(desc, which, full, shards, stream=None):
+    _check(load().virtual_cube_scatter(ctypes.byref(desc), which, _ptr(full), _ptr(shards), _stream(stream)),
+           "virtual_cube_scatter")
+    return shards
+
+
+def virtual_cube_assemble(desc, which, shards, full, stream=None):
+    _check(load().virtual_cube_assemble(ctypes.byref(desc), which, _ptr(shards), _ptr(full), _stream(stream)),
+           "virtual_cube_assemble")
+    return full

@@ -1,0 +1,241 @@
+// C-ABI entry points: argument validation on the host, then dispatch to the
+// kernels.  Nothing here touches the device before every check has passed.
+#include "common.h"
+
+using namespace cube3d;
+
+namespace {
+
+int elem_size(int dtype)
+{
+    switch (dtype) {
+    case CUBE3D_F32: return 4;
+    case CUBE3D_BF16: return 2;
+    case CUBE3D_FP8_E4M3: return 1;
+    default: return 0;
+    }
+}
+
+int check_desc(const cube3d_desc *d, CubeGeom *g)
+{
+    if (!d) return CUBE3D_EINVAL;
+    if (d->q < 1) return CUBE3D_EINVAL;
+    if (d->in_axis != CUBE3D_AXIS_Y && d->in_axis != CUBE3D_AXIS_Z) return CUBE3D_EINVAL;
+    if (d->q > 40) return CUBE3D_ESHAPE;  // q^3 processors must fit a grid dimension
+    if (d->M < 1 || d->K < 1 || d->N < 1) return CUBE3D_ESHAPE;
+    const int64_t q = d->q, q2 = q * q;
+    if (d->M % q2 || d->N % q2 || d->K % q) return CUBE3D_ESHAPE;
+    if (elem_size(d->in_dtype) == 0) return CUBE3D_EDTYPE;
+    if (d->out_dtype != CUBE3D_F32 && d->out_dtype != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    if (d->shard_dtype != CUBE3D_F32 && d->shard_dtype != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    if (d->in_dtype == CUBE3D_FP8_E4M3) {
+        const float s[3] = {d->scale_x, d->scale_w, d->scale_dy};
+        for (float v : s)
+            if (!(v > 0.f) || v > 3.0e38f) return CUBE3D_EINVAL;
+    }
+    if (g) {
+        g->q = d->q;
+        g->in_axis_z = d->in_axis == CUBE3D_AXIS_Z;
+        g->M = d->M; g->K = d->K; g->N = d->N;
+        g->Mb = d->M / q; g->Kb = d->K / q; g->Nb = d->N / q;
+        g->Ms = d->M / q2; g->Ns = d->N / q2;
+    }
+    return CUBE3D_OK;
+}
+
+// 1 = one processor, q^3 = all of them; negative = error
+int check_coords(const cube3d_desc *d, int i, int j, int l)
+{
+    if (i == -1 && j == -1 && l == -1) return d->q * d->q * d->q;
+    if (i < 0 || j < 0 || l < 0 || i >= d->q || j >= d->q || l >= d->q) return CUBE3D_EINVAL;
+    return 1;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int build_gemm(const cube3d_desc *d, int op, int batch, const void *A, const void *B, void *C, void *ws,
+               size_t ws_bytes, void *stream, GemmArgs *out)
+{
+    CubeGeom g;
+    int rc = check_desc(d, &g);
+    if (rc != CUBE3D_OK) return rc;
+    GemmArgs a{};
+    a.A = A; a.B = B; a.C = C;
+    a.batch = batch;
+    a.in_dtype = d->in_dtype;
+    a.out_dtype = d->out_dtype;
+    a.workspace = ws;
+    a.workspace_bytes = ws_bytes;
+    a.stream = static_cast<hipStream_t>(stream);
+    const bool fp8 = d->in_dtype == CUBE3D_FP8_E4M3;
+    switch (op) {
+    case CUBE3D_OP_FWD:      // P[Mb,Nb] = X[Mb,Kb] W[Kb,Nb]
+        a.Mo = g.Mb; a.No = g.Nb; a.Kc = g.Kb;
+        a.a_kmajor = true; a.b_kmajor = false;
+        a.lda = g.Kb; a.ldb = g.Nb; a.ldc = g.Nb;
+        a.alpha = fp8 ? d->scale_x * d->scale_w : 1.f;
+        break;
+    case CUBE3D_OP_BWD_DX:   // Q[Mb,Kb] = dY[Mb,Nb] W[Kb,Nb]^T
+        a.Mo = g.Mb; a.No = g.Kb; a.Kc = g.Nb;
+        a.a_kmajor = true; a.b_kmajor = true;
+        a.lda = g.Nb; a.ldb = g.Nb; a.ldc = g.Kb;
+        a.alpha = fp8 ? d->scale_dy * d->scale_w : 1.f;
+        break;
+    case CUBE3D_OP_BWD_DW:   // R[Kb,Nb] = X[Mb,Kb]^T dY[Mb,Nb]
+        a.Mo = g.Kb; a.No = g.Nb; a.Kc = g.Mb;
+        a.a_kmajor = false; a.b_kmajor = false;
+        a.lda = g.Kb; a.ldb = g.Nb; a.ldc = g.Nb;
+        a.alpha = fp8 ? d->scale_x * d->scale_dy : 1.f;
+        break;
+    default: return CUBE3D_EINVAL;
+    }
+    // batch strides: one packed block per processor
+    a.strideA = (a.a_kmajor ? a.Mo : a.Kc) * a.lda;
+    a.strideB = (a.b_kmajor ? a.No : a.Kc) * a.ldb;
+    a.strideC = a.Mo * a.ldc;
+    *out = a;
+    return CUBE3D_OK;
+}
+
+size_t workspace_for(const GemmArgs &a)
+{
+    if (a.in_dtype == CUBE3D_BF16) return gemm_bf16_fast_workspace(a);
+    return 0;
+}
+
+int run_product(const cube3d_desc *d, int op, int i, int j, int l, const void *A, const void *B, void *C, void *ws,
+                size_t ws_bytes, void *stream)
+{
+    int rc = check_desc(d, nullptr);
+    if (rc != CUBE3D_OK) return rc;
+    const int batch = check_coords(d, i, j, l);
+    if (batch < 0) return batch;
+    if (!A || !B || !C) return CUBE3D_EINVAL;
+    if (misaligned(A) || misaligned(B) || misaligned(C) || misaligned(ws)) return CUBE3D_EINVAL;
+    GemmArgs a;
+    rc = build_gemm(d, op, batch, A, B, C, ws, ws_bytes, stream, &a);
+    if (rc != CUBE3D_OK) return rc;
+    const size_t need = workspace_for(a);
+    if (need > 0 && (!ws || ws_bytes < need)) return CUBE3D_EWORKSPACE;
+    if (a.in_dtype == CUBE3D_BF16) {
+        rc = gemm_bf16_fast(a);
+        if (rc != CUBE3D_ENOTIMPL) return rc;
+    } else if (a.in_dtype == CUBE3D_FP8_E4M3) {
+        rc = gemm_fp8_fast(a);
+        if (rc != CUBE3D_ENOTIMPL) return rc;
+    }
+    return gemm_generic(a);
+}
+
+}  // namespace
+
+extern "C" {
+
+int cube3d_linear_fwd(const cube3d_desc *desc, int i, int j, int l, const void *X_block, const void *W_block, void *P,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_product(desc, CUBE3D_OP_FWD, i, j, l, X_block, W_block, P, workspace, workspace_bytes, stream);
+}
+
+int cube3d_linear_bwd_dx(const cube3d_desc *desc, int i, int j, int l, const void *dY_block, const void *W_block,
+                         void *Q, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_product(desc, CUBE3D_OP_BWD_DX, i, j, l, dY_block, W_block, Q, workspace, workspace_bytes, stream);
+}
+
+int cube3d_linear_bwd_dw(const cube3d_desc *desc, int i, int j, int l, const void *X_block, const void *dY_block,
+                         void *R, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_product(desc, CUBE3D_OP_BWD_DW, i, j, l, X_block, dY_block, R, workspace, workspace_bytes, stream);
+}
+
+size_t cube3d_workspace_bytes(const cube3d_desc *desc, int op, int batched)
+{
+    if (check_desc(desc, nullptr) != CUBE3D_OK) return 0;
+    GemmArgs a;
+    const int batch = batched ? desc->q * desc->q * desc->q : 1;
+    if (build_gemm(desc, op, batch, nullptr, nullptr, nullptr, nullptr, 0, nullptr, &a) != CUBE3D_OK) return 0;
+    return workspace_for(a);
+}
+
+int virtual_cube_gather(const cube3d_desc *desc, int which, int axis, const void *shards, void *gathered, void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(desc, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!shards || !gathered || misaligned(shards) || misaligned(gathered)) return CUBE3D_EINVAL;
+    const int out_axis = desc->in_axis == CUBE3D_AXIS_Y ? CUBE3D_AXIS_Z : CUBE3D_AXIS_Y;
+    int mode;
+    switch (which) {
+    case CUBE3D_OPERAND_X: if (axis != desc->in_axis) return CUBE3D_EINVAL; mode = MV_GATHER_X; break;
+    case CUBE3D_OPERAND_W: if (axis != CUBE3D_AXIS_X) return CUBE3D_EINVAL; mode = MV_GATHER_W; break;
+    case CUBE3D_OPERAND_DY: if (axis != out_axis) return CUBE3D_EINVAL; mode = MV_GATHER_DY; break;
+    default: return CUBE3D_EINVAL;
+    }
+    return cube_move(g, mode, elem_size(desc->in_dtype), shards, gathered, static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_reduce_scatter(const cube3d_desc *desc, int which, int axis, const void *partials, void *shards,
+                                void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(desc, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!partials || !shards || misaligned(partials) || misaligned(shards)) return CUBE3D_EINVAL;
+    const int out_axis = desc->in_axis == CUBE3D_AXIS_Y ? CUBE3D_AXIS_Z : CUBE3D_AXIS_Y;
+    int mode;
+    switch (which) {
+    case CUBE3D_OPERAND_Y: if (axis != out_axis) return CUBE3D_EINVAL; mode = MV_REDUCE_Y; break;
+    case CUBE3D_OPERAND_DX: if (axis != desc->in_axis) return CUBE3D_EINVAL; mode = MV_REDUCE_DX; break;
+    case CUBE3D_OPERAND_DW: if (axis != CUBE3D_AXIS_X) return CUBE3D_EINVAL; mode = MV_REDUCE_DW; break;
+    default: return CUBE3D_EINVAL;
+    }
+    return cube_reduce(g, mode, desc->out_dtype, desc->shard_dtype, partials, shards, static_cast<hipStream_t>(stream));
+}
+
+static int storage_move(const cube3d_desc *desc, int which, bool scatter, const void *src, void *dst, void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(desc, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!src || !dst || misaligned(src) || misaligned(dst)) return CUBE3D_EINVAL;
+    int mode, es;
+    switch (which) {
+    case CUBE3D_OPERAND_X: mode = scatter ? MV_SCATTER_X : MV_ASSEMBLE_X; es = elem_size(desc->in_dtype); break;
+    case CUBE3D_OPERAND_W: mode = scatter ? MV_SCATTER_W : MV_ASSEMBLE_W; es = elem_size(desc->in_dtype); break;
+    case CUBE3D_OPERAND_DY: mode = scatter ? MV_SCATTER_Y : MV_ASSEMBLE_Y; es = elem_size(desc->in_dtype); break;
+    case CUBE3D_OPERAND_Y: mode = scatter ? MV_SCATTER_Y : MV_ASSEMBLE_Y; es = elem_size(desc->shard_dtype); break;
+    case CUBE3D_OPERAND_DX: mode = scatter ? MV_SCATTER_X : MV_ASSEMBLE_X; es = elem_size(desc->shard_dtype); break;
+    case CUBE3D_OPERAND_DW: mode = scatter ? MV_SCATTER_W : MV_ASSEMBLE_W; es = elem_size(desc->shard_dtype); break;
+    default: return CUBE3D_EINVAL;
+    }
+    return cube_move(g, mode, es, src, dst, static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_scatter(const cube3d_desc *desc, int which, const void *full, void *shards, void *stream)
+{
+    return storage_move(desc, which, true, full, shards, stream);
+}
+
+int virtual_cube_assemble(const cube3d_desc *desc, int which, const void *shards, void *full, void *stream)
+{
+    return storage_move(desc, which, false, shards, full, stream);
+}
+
+const char *cube3d_status_string(int status)
+{
+    switch (status) {
+    case CUBE3D_OK: return "ok";
+    case CUBE3D_EINVAL: return "invalid argument (null or misaligned pointer, bad enum, bad rank coordinates or scale)";
+    case CUBE3D_ESHAPE: return "bad shape (q^2 must divide M and N, q must divide K, sizes positive)";
+    case CUBE3D_EDTYPE: return "unsupported dtype combination";
+    case CUBE3D_EWORKSPACE: return "workspace too small";
+    case CUBE3D_ELAUNCH: return "HIP launch failed";
+    case CUBE3D_ENOTIMPL: return "not implemented";
+    default: return "unknown status";
+    }
+}
+
+int cube3d_version(void) { return CUBE3D_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,269 @@
+// Virtual-cube data movement: the load-balanced storage of Section 3.1.1
+// (scatter / assemble), the all-gathers of Algorithm 1 steps 1-2 (and of dY for
+// Algorithm 2), and the reduce-scatters of Algorithm 1 step 4 and Algorithm 2.
+// All q^3 processors' buffers live in this GPU's memory, so every "collective"
+// is a streaming copy or a streaming sum: HBM-bandwidth work, no matrix cores.
+//
+// Work decomposition: blockIdx.z = destination processor r, blockIdx.x = a group
+// of destination rows; each wavefront takes whole rows, its lanes stride over
+// 16-byte pieces of the row.  All index decoding is wave-uniform.
+#include "common.h"
+
+namespace cube3d {
+
+namespace {
+
+constexpr int ROWS_PER_BLOCK = 16;
+
+struct Coords {
+    int i, a, b;
+};
+
+__device__ __forceinline__ Coords decode_rank(const CubeGeom &g, int r)
+{
+    const int l = r % g.q;
+    const int j = (r / g.q) % g.q;
+    Coords c;
+    c.i = r / (g.q * g.q);
+    c.a = g.in_axis_z ? l : j;
+    c.b = g.in_axis_z ? j : l;
+    return c;
+}
+
+__device__ __forceinline__ int64_t rank_index(const CubeGeom &g, int i, int a, int b)
+{
+    return g.in_axis_z ? ((int64_t)(i * g.q + b) * g.q + a) : ((int64_t)(i * g.q + a) * g.q + b);
+}
+
+// For destination row `row` of processor r: element offsets of the row in the
+// destination and of its first source segment; `seg` = elements per contiguous
+// source segment, `seg_stride` = source distance between consecutive segments
+// of the same destination row (only the W gather has more than one).
+struct RowMap {
+    int64_t dst, src, seg, seg_stride;
+};
+
+__device__ __forceinline__ RowMap map_copy_row(const CubeGeom &g, int mode, int r, int64_t row)
+{
+    const Coords c = decode_rank(g, r);
+    RowMap m;
+    m.seg_stride = 0;
+    switch (mode) {
+    case MV_GATHER_X: {  // dst [Mb,Kb]; row panel a' comes from processor (i, a', b)
+        const int64_t a2 = row / g.Ms, rr = row - a2 * g.Ms;
+        m.seg = g.Kb;
+        m.dst = ((int64_t)r * g.Mb + row) * g.Kb;
+        m.src = (rank_index(g, c.i, (int)a2, c.b) * g.Ms + rr) * g.Kb;
+        break;
+    }
+    case MV_GATHER_DY: {  // dst [Mb,Nb]; row panel b' comes from processor (i, a, b')
+        const int64_t b2 = row / g.Ms, rr = row - b2 * g.Ms;
+        m.seg = g.Nb;
+        m.dst = ((int64_t)r * g.Mb + row) * g.Nb;
+        m.src = (rank_index(g, c.i, c.a, (int)b2) * g.Ms + rr) * g.Nb;
+        break;
+    }
+    case MV_GATHER_W: {  // dst [Kb,Nb]; column panel i' comes from processor (i', a, b)
+        m.seg = g.Ns;
+        m.dst = ((int64_t)r * g.Kb + row) * g.Nb;
+        m.src = (rank_index(g, 0, c.a, c.b) * g.Kb + row) * g.Ns;
+        m.seg_stride = (rank_index(g, 1 % g.q, c.a, c.b) - rank_index(g, 0, c.a, c.b)) * g.Kb * g.Ns;
+        break;
+    }
+    case MV_SCATTER_X:
+    case MV_ASSEMBLE_X: {
+        m.seg = g.Kb;
+        const int64_t sh = ((int64_t)r * g.Ms + row) * g.Kb;
+        const int64_t fu = ((int64_t)c.i * g.Mb + (int64_t)c.a * g.Ms + row) * g.K + (int64_t)c.b * g.Kb;
+        m.dst = mode == MV_SCATTER_X ? sh : fu;
+        m.src = mode == MV_SCATTER_X ? fu : sh;
+        break;
+    }
+    case MV_SCATTER_W:
+    case MV_ASSEMBLE_W: {
+        m.seg = g.Ns;
+        const int64_t sh = ((int64_t)r * g.Kb + row) * g.Ns;
+        const int64_t fu = ((int64_t)c.b * g.Kb + row) * g.N + (int64_t)c.a * g.Nb + (int64_t)c.i * g.Ns;
+        m.dst = mode == MV_SCATTER_W ? sh : fu;
+        m.src = mode == MV_SCATTER_W ? fu : sh;
+        break;
+    }
+    default: {  // MV_SCATTER_Y / MV_ASSEMBLE_Y
+        m.seg = g.Nb;
+        const int64_t sh = ((int64_t)r * g.Ms + row) * g.Nb;
+        const int64_t fu = ((int64_t)c.i * g.Mb + (int64_t)c.b * g.Ms + row) * g.N + (int64_t)c.a * g.Nb;
+        m.dst = mode == MV_SCATTER_Y ? sh : fu;
+        m.src = mode == MV_SCATTER_Y ? fu : sh;
+        break;
+    }
+    }
+    return m;
+}
+
+// VEC = bytes moved per lane per step; es = element size in bytes.
+template <typename VecT>
+__global__ __launch_bounds__(256) void cube_copy_kernel(CubeGeom g, int mode, int64_t rows, int nseg, int es,
+                                                        const char *__restrict__ src, char *__restrict__ dst)
+{
+    const int r = blockIdx.z;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK;
+    for (int w = wave; w < ROWS_PER_BLOCK; w += 4) {
+        const int64_t row = row0 + w;
+        if (row >= rows) break;
+        const RowMap m = map_copy_row(g, mode, r, row);
+        const int64_t seg_vecs = m.seg * es / (int64_t)sizeof(VecT);
+        const VecT *s = reinterpret_cast<const VecT *>(src + m.src * es);
+        VecT *d = reinterpret_cast<VecT *>(dst + m.dst * es);
+        const int64_t stride_vecs = m.seg_stride * es / (int64_t)sizeof(VecT);
+        const int64_t total = seg_vecs * nseg;
+        for (int64_t c = lane; c < total; c += 64) {
+            const int64_t p = c / seg_vecs;
+            d[c] = s[p * stride_vecs + (c - p * seg_vecs)];
+        }
+    }
+}
+
+template <typename T> __device__ __forceinline__ float load_f32(const T *p);
+template <> __device__ __forceinline__ float load_f32<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float load_f32<unsigned short>(const unsigned short *p)
+{
+    return bf16_bits_to_f32(*p);
+}
+template <typename T> __device__ __forceinline__ void store_f32(T *p, float v);
+template <> __device__ __forceinline__ void store_f32<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_f32<unsigned short>(unsigned short *p, float v)
+{
+    *p = f32_to_bf16_bits(v);
+}
+
+template <typename T, int V> struct __attribute__((aligned(sizeof(T) * V))) Pack {
+    T v[V];
+};
+
+// Sum over the q partials of a reduce direction, fp32, ascending index, one
+// rounding at the store.  V elements per lane per step.
+template <typename TIn, typename TOut, int V>
+__global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, int64_t rows,
+                                                          const TIn *__restrict__ partials, TOut *__restrict__ shards)
+{
+    const int r = blockIdx.z;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const Coords c = decode_rank(g, r);
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK;
+
+    int64_t seg, src0, src_step, src_ld, dst_ld, src_row0, src_col0;
+    if (mode == MV_REDUCE_Y) {  // keep row panel b of the sum over b'
+        seg = g.Nb; dst_ld = g.Nb; src_ld = g.Nb; src_row0 = (int64_t)c.b * g.Ms; src_col0 = 0;
+        src0 = rank_index(g, c.i, c.a, 0) * g.Mb * g.Nb;
+        src_step = (rank_index(g, c.i, c.a, 1 % g.q) - rank_index(g, c.i, c.a, 0)) * g.Mb * g.Nb;
+    } else if (mode == MV_REDUCE_DX) {  // keep row panel a of the sum over a'
+        seg = g.Kb; dst_ld = g.Kb; src_ld = g.Kb; src_row0 = (int64_t)c.a * g.Ms; src_col0 = 0;
+        src0 = rank_index(g, c.i, 0, c.b) * g.Mb * g.Kb;
+        src_step = (rank_index(g, c.i, 1 % g.q, c.b) - rank_index(g, c.i, 0, c.b)) * g.Mb * g.Kb;
+    } else {  // MV_REDUCE_DW: keep column panel i of the sum over i'
+        seg = g.Ns; dst_ld = g.Ns; src_ld = g.Nb; src_row0 = 0; src_col0 = (int64_t)c.i * g.Ns;
+        src0 = rank_index(g, 0, c.a, c.b) * g.Kb * g.Nb;
+        src_step = (rank_index(g, 1 % g.q, c.a, c.b) - rank_index(g, 0, c.a, c.b)) * g.Kb * g.Nb;
+    }
+    const int64_t dst_rows = mode == MV_REDUCE_DW ? g.Kb : g.Ms;
+
+    for (int w = wave; w < ROWS_PER_BLOCK; w += 4) {
+        const int64_t row = row0 + w;
+        if (row >= rows) break;
+        const TIn *s = partials + src0 + (src_row0 + row) * src_ld + src_col0;
+        TOut *d = shards + ((int64_t)r * dst_rows + row) * dst_ld;
+        for (int64_t e = (int64_t)lane * V; e < seg; e += 64 * V) {
+            float acc[V];
+            {
+                const Pack<TIn, V> p = *reinterpret_cast<const Pack<TIn, V> *>(s + e);
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] = load_f32<TIn>(&p.v[v]);
+            }
+            for (int k = 1; k < g.q; ++k) {
+                const Pack<TIn, V> p = *reinterpret_cast<const Pack<TIn, V> *>(s + k * src_step + e);
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += load_f32<TIn>(&p.v[v]);
+            }
+            Pack<TOut, V> o;
+#pragma unroll
+            for (int v = 0; v < V; ++v) store_f32<TOut>(&o.v[v], acc[v]);
+            *reinterpret_cast<Pack<TOut, V> *>(d + e) = o;
+        }
+    }
+}
+
+template <typename TIn, typename TOut>
+int launch_reduce(const CubeGeom &g, int mode, int64_t rows, int64_t seg, const void *partials, void *shards,
+                  hipStream_t stream)
+{
+    dim3 grid((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), 1, (unsigned)(g.q * g.q * g.q));
+    const TIn *p = static_cast<const TIn *>(partials);
+    TOut *s = static_cast<TOut *>(shards);
+    if (seg % 4 == 0)
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 4>), grid, dim3(256), 0, stream, g, mode, rows, p, s);
+    else
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 1>), grid, dim3(256), 0, stream, g, mode, rows, p, s);
+    return launch_status();
+}
+
+}  // namespace
+
+// rows: destination rows per processor; nseg: source segments per destination row
+int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, hipStream_t stream)
+{
+    int64_t rows, seg;
+    int nseg = 1;
+    switch (mode) {
+    case MV_GATHER_X: rows = g.Mb; seg = g.Kb; break;
+    case MV_GATHER_DY: rows = g.Mb; seg = g.Nb; break;
+    case MV_GATHER_W: rows = g.Kb; seg = g.Ns; nseg = g.q; break;
+    case MV_SCATTER_X: case MV_ASSEMBLE_X: rows = g.Ms; seg = g.Kb; break;
+    case MV_SCATTER_W: case MV_ASSEMBLE_W: rows = g.Kb; seg = g.Ns; break;
+    case MV_SCATTER_Y: case MV_ASSEMBLE_Y: rows = g.Ms; seg = g.Nb; break;
+    default: return CUBE3D_EINVAL;
+    }
+    const int64_t nblk = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    if (nblk > 0x7fffffff || g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;
+    dim3 grid((unsigned)nblk, 1, (unsigned)(g.q * g.q * g.q));
+    const char *s = static_cast<const char *>(src);
+    char *d = static_cast<char *>(dst);
+    const int64_t seg_bytes = seg * es;
+    // every segment start is a multiple of the segment length, so alignment of the
+    // segment length decides the widest safe vector
+    if (seg_bytes % 16 == 0)
+        hipLaunchKernelGGL((cube_copy_kernel<i32x4>), grid, dim3(256), 0, stream, g, mode, rows, nseg, es, s, d);
+    else if (seg_bytes % 4 == 0)
+        hipLaunchKernelGGL((cube_copy_kernel<int>), grid, dim3(256), 0, stream, g, mode, rows, nseg, es, s, d);
+    else if (seg_bytes % 2 == 0)
+        hipLaunchKernelGGL((cube_copy_kernel<short>), grid, dim3(256), 0, stream, g, mode, rows, nseg, es, s, d);
+    else
+        hipLaunchKernelGGL((cube_copy_kernel<char>), grid, dim3(256), 0, stream, g, mode, rows, nseg, es, s, d);
+    return launch_status();
+}
+
+int cube_reduce(const CubeGeom &g, int mode, int partial_dtype, int shard_dtype, const void *partials, void *shards,
+                hipStream_t stream)
+{
+    int64_t rows, seg;
+    switch (mode) {
+    case MV_REDUCE_Y: rows = g.Ms; seg = g.Nb; break;
+    case MV_REDUCE_DX: rows = g.Ms; seg = g.Kb; break;
+    case MV_REDUCE_DW: rows = g.Kb; seg = g.Ns; break;
+    default: return CUBE3D_EINVAL;
+    }
+    if (g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;
+    if (partial_dtype == CUBE3D_F32 && shard_dtype == CUBE3D_F32)
+        return launch_reduce<float, float>(g, mode, rows, seg, partials, shards, stream);
+    if (partial_dtype == CUBE3D_F32 && shard_dtype == CUBE3D_BF16)
+        return launch_reduce<float, unsigned short>(g, mode, rows, seg, partials, shards, stream);
+    if (partial_dtype == CUBE3D_BF16 && shard_dtype == CUBE3D_F32)
+        return launch_reduce<unsigned short, float>(g, mode, rows, seg, partials, shards, stream);
+    if (partial_dtype == CUBE3D_BF16 && shard_dtype == CUBE3D_BF16)
+        return launch_reduce<unsigned short, unsigned short>(g, mode, rows, seg, partials, shards, stream);
+    return CUBE3D_EDTYPE;
+}
+
+}  // namespace cube3d

@@ -1,0 +1,305 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bit-exact on integer inputs in [-4, 4]; within the stated tolerance
+(max |err| / max |ref| <= 1e-5 for fp32, 2e-2 for bf16 and fp8) on real data.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2105_14450_amd as c3
+from oracle import matmul as om
+from oracle import numfmt
+from oracle.layout import Cube
+from paper_2105_14450_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+AX = {"y": c3.AXIS_Y, "z": c3.AXIS_Z}
+
+
+def _decode_inputs(inp, dtype):
+    return {k: numfmt.decode(raw, dtype, scale) for k, (raw, scale) in inp.items()}
+
+
+def _desc(q, M, K, N, dtype, out_dtype, shard_dtype, ax, inp):
+    return c3.make_desc(q, M, K, N, in_dtype=gu.CODE[dtype], out_dtype=gu.CODE[out_dtype],
+                        shard_dtype=gu.CODE[shard_dtype], in_axis=AX[ax],
+                        scale_x=inp["X"][1], scale_w=inp["W"][1], scale_dy=inp["dY"][1])
+
+
+def _check(got, ref, dtype, exact, what):
+    if exact:
+        assert np.array_equal(got, ref), "%s: not bit-exact on integer data (max diff %g)" % (
+            what, np.max(np.abs(got - ref)))
+    else:
+        err = gu.scaled_max_err(got, ref)
+        assert err <= gu.TOL[dtype], "%s: scaled max error %g > %g" % (what, err, gu.TOL[dtype])
+
+
+def run_virtual_cube(q, M, K, N, dtype, dist, seed, ax="y", out_dtype="f32", shard_dtype=None):
+    """Whole path on the virtual cube: scatter, gathers, three batched products,
+    reduce-scatters, assemble; every intermediate buffer compared with the oracle."""
+    shard_dtype = shard_dtype or ("f32" if dtype == "f32" else "bf16")
+    exact = dist == "int"
+    inp = synth.linear_inputs(M, K, N, dtype, dist, seed)
+    val = _decode_inputs(inp, dtype)
+    cube = Cube(q, M, K, N, ax)
+    d = _desc(q, M, K, N, dtype, out_dtype, shard_dtype, ax, inp)
+    out_axis = c3.AXIS_Z if ax == "y" else c3.AXIS_Y
+    st = gu.TORCH_STORAGE[dtype]
+    n = q ** 3
+
+    # a0: storage
+    dev = {k: gu.to_device(raw) for k, (raw, _) in inp.items()}
+    xs = gu.empty((n, cube.Ms, cube.Kb), dtype)
+    ws = gu.empty((n, cube.Kb, cube.Ns), dtype)
+    gs = gu.empty((n, cube.Ms, cube.Nb), dtype)
+    c3.virtual_cube_scatter(d, c3.OPERAND_X, dev["X"], xs)
+    c3.virtual_cube_scatter(d, c3.OPERAND_W, dev["W"], ws)
+    c3.virtual_cube_scatter(d, c3.OPERAND_DY, dev["dY"], gs)
+    assert np.array_equal(gu.raw_host(xs).reshape(q, q, q, cube.Ms, cube.Kb), cube.shard_x(inp["X"][0]))
+    assert np.array_equal(gu.raw_host(ws).reshape(q, q, q, cube.Kb, cube.Ns), cube.shard_w(inp["W"][0]))
+    assert np.array_equal(gu.raw_host(gs).reshape(q, q, q, cube.Ms, cube.Nb), cube.shard_y(inp["dY"][0]))
+
+    # a1, a2, a5: all-gathers
+    xb = gu.empty((n, cube.Mb, cube.Kb), dtype)
+    wb = gu.empty((n, cube.Kb, cube.Nb), dtype)
+    gb = gu.empty((n, cube.Mb, cube.Nb), dtype)
+    c3.virtual_cube_gather(d, c3.OPERAND_X, AX[ax], xs, xb)
+    c3.virtual_cube_gather(d, c3.OPERAND_W, c3.AXIS_X, ws, wb)
+    c3.virtual_cube_gather(d, c3.OPERAND_DY, out_axis, gs, gb)
+    assert np.array_equal(gu.raw_host(xb).reshape(q, q, q, cube.Mb, cube.Kb), cube.block_x(inp["X"][0]))
+    assert np.array_equal(gu.raw_host(wb).reshape(q, q, q, cube.Kb, cube.Nb), cube.block_w(inp["W"][0]))
+    assert np.array_equal(gu.raw_host(gb).reshape(q, q, q, cube.Mb, cube.Nb), cube.block_y(inp["dY"][0]))
+
+    # a3, a6, a8: the three local products on all q^3 processors at once
+    P = gu.empty((n, cube.Mb, cube.Nb), out_dtype)
+    Q = gu.empty((n, cube.Mb, cube.Kb), out_dtype)
+    R = gu.empty((n, cube.Kb, cube.Nb), out_dtype)
+    c3.cube3d_linear_fwd(d, c3.ALL_RANKS, xb, wb, P, gu.workspace(d, c3.OP_FWD, True))
+    c3.cube3d_linear_bwd_dx(d, c3.ALL_RANKS, gb, wb, Q, gu.workspace(d, c3.OP_BWD_DX, True))
+    c3.cube3d_linear_bwd_dw(d, c3.ALL_RANKS, xb, gb, R, gu.workspace(d, c3.OP_BWD_DW, True))
+    bx, bw, bg = cube.block_x(val["X"]), cube.block_w(val["W"]), cube.block_y(val["dY"])
+    Ph, Qh, Rh = gu.to_host(P, out_dtype), gu.to_host(Q, out_dtype), gu.to_host(R, out_dtype)
+    Pref = np.empty((q, q, q, cube.Mb, cube.Nb))
+    Qref = np.empty((q, q, q, cube.Mb, cube.Kb))
+    Rref = np.empty((q, q, q, cube.Kb, cube.Nb))
+    for r in cube.ranks():
+        Pref[r] = om.forward(bx[r], bw[r], 4)
+        Qref[r] = om.backward_dx(bg[r], bw[r], 4)
+        Rref[r] = om.backward_dw(bx[r], bg[r], 4)
+    for got, ref, name in ((Ph, Pref, "P"), (Qh, Qref, "Q"), (Rh, Rref, "R")):
+        _check(got.reshape(ref.shape), numfmt.round_to(ref, out_dtype) if exact else ref, dtype, exact,
+               "partial product " + name)
+
+    # a4, a7, a9: reduce-scatters; then collect the full matrices
+    ys = gu.empty((n, cube.Ms, cube.Nb), shard_dtype)
+    dxs = gu.empty((n, cube.Ms, cube.Kb), shard_dtype)
+    dws = gu.empty((n, cube.Kb, cube.Ns), shard_dtype)
+    c3.virtual_cube_reduce_scatter(d, c3.OPERAND_Y, out_axis, P, ys)
+    c3.virtual_cube_reduce_scatter(d, c3.OPERAND_DX, AX[ax], Q, dxs)
+    c3.virtual_cube_reduce_scatter(d, c3.OPERAND_DW, c3.AXIS_X, R, dws)
+    Yf = gu.empty((M, N), shard_dtype)
+    dXf = gu.empty((M, K), shard_dtype)
+    dWf = gu.empty((K, N), shard_dtype)
+    c3.virtual_cube_assemble(d, c3.OPERAND_Y, ys, Yf)
+    c3.virtual_cube_assemble(d, c3.OPERAND_DX, dxs, dXf)
+    c3.virtual_cube_assemble(d, c3.OPERAND_DW, dws, dWf)
+    torch.cuda.synchronize()
+    if exact:
+        # partial products are stored in out_dtype before they are summed: on integer data the
+        # sum of the stored partials is exact, so the expected bits are those of that sum
+        Y = cube.unshard_y(cube.reduce_scatter_y(numfmt.round_to(Pref, out_dtype)))
+        dX = cube.unshard_x(cube.reduce_scatter_dx(numfmt.round_to(Qref, out_dtype)))
+        dW = cube.unshard_w(cube.reduce_scatter_dw(numfmt.round_to(Rref, out_dtype)))
+        if out_dtype == "f32":      # nothing was rounded: this is the plain product
+            assert np.array_equal(Y, om.forward(val["X"], val["W"], 4))
+            assert np.array_equal(dX, om.backward_dx(val["dY"], val["W"], 4))
+            assert np.array_equal(dW, om.backward_dw(val["X"], val["dY"], 4))
+    else:
+        Y, dX, dW = om.forward(val["X"], val["W"], 4), om.backward_dx(val["dY"], val["W"], 4), \
+            om.backward_dw(val["X"], val["dY"], 4)
+    for got_s, got_f, ref, shard, name in ((ys, Yf, Y, cube.shard_y, "Y"), (dxs, dXf, dX, cube.shard_x, "dX"),
+                                           (dws, dWf, dW, cube.shard_w, "dW")):
+        ref_r = numfmt.round_to(ref, shard_dtype) if exact else ref
+        _check(gu.to_host(got_f, shard_dtype), ref_r, dtype, exact, "assembled " + name)
+        _check(gu.to_host(got_s, shard_dtype).reshape(shard(ref_r).shape), shard(ref_r), dtype, exact,
+               "shards of " + name)
+
+
+# ---- config 1: virtual cube q=2, fp32, X [256,128], W [128,128] -------------------------------
+@pytest.mark.parametrize("ax", ["y", "z"])
+@pytest.mark.parametrize("dist,seed", [("uniform", 1), ("int", 101)])
+def test_config1_virtual_cube_fp32(dist, seed, ax):
+    run_virtual_cube(2, 256, 128, 128, "f32", dist, seed, ax)
+
+
+# ---- ragged shapes: block sizes that are not multiples of any tile ----------------------------
+@pytest.mark.parametrize("dtype,out_dtype,shard_dtype", [("f32", "f32", "f32"), ("bf16", "f32", "bf16"),
+                                                        ("bf16", "bf16", "f32"), ("fp8_e4m3", "f32", "bf16"),
+                                                        ("fp8_e4m3", "bf16", "bf16")])
+@pytest.mark.parametrize("dist,seed", [("normal", 7), ("int", 107)])
+def test_ragged_virtual_cube(dtype, out_dtype, shard_dtype, dist, seed):
+    # q=3: Mb=150, Kb=45, Nb=51, Ms=50, Ns=17 (odd segment lengths, several tiles plus tails)
+    run_virtual_cube(3, 450, 135, 153, dtype, dist, seed, "z" if seed == 7 else "y", out_dtype, shard_dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "fp8_e4m3"])
+def test_degenerate_cubes(dtype):
+    run_virtual_cube(1, 5, 3, 7, dtype, "int", 11)            # q = 1: one plain product, tiny
+    run_virtual_cube(2, 4, 2, 4, dtype, "int", 12, "z")       # shards of a single row / column
+    run_virtual_cube(2, 8, 66, 8, dtype, "normal", 13)        # contraction longer than the output
+
+
+# ---- one processor's share, called with its coordinates ---------------------------------------
+def run_rank_share(q, M, K, N, dtype, dist, seed, rank, out_dtype="f32", samples=None, twice=False):
+    """One processor's three products at their real shape; full compare, or `samples` sampled entries."""
+    exact = dist == "int"
+    Mb, Kb, Nb = M // q, K // q, N // q
+    integer = dist == "int"
+    sig_w = 0.02 if dist == "normal" else 1.0
+    X = synth.store(synth.draw((Mb, Kb), dist, seed, synth.TID_X), dtype, integer)
+    W = synth.store(synth.draw((Kb, Nb), dist, seed, synth.TID_W, sig_w), dtype, integer)
+    G = synth.store(synth.draw((Mb, Nb), dist, seed, synth.TID_DY), dtype, integer)
+    inp = {"X": X, "W": W, "dY": G}
+    d = _desc(q, M, K, N, dtype, out_dtype, "bf16" if dtype != "f32" else "f32", "y", inp)
+    xb, wb, gb = gu.to_device(X[0]), gu.to_device(W[0]), gu.to_device(G[0])
+    P, Qo, R = gu.empty((Mb, Nb), out_dtype), gu.empty((Mb, Kb), out_dtype), gu.empty((Kb, Nb), out_dtype)
+
+    def run():
+        c3.cube3d_linear_fwd(d, rank, xb, wb, P, gu.workspace(d, c3.OP_FWD, False))
+        c3.cube3d_linear_bwd_dx(d, rank, gb, wb, Qo, gu.workspace(d, c3.OP_BWD_DX, False))
+        c3.cube3d_linear_bwd_dw(d, rank, xb, gb, R, gu.workspace(d, c3.OP_BWD_DW, False))
+        torch.cuda.synchronize()
+        return [gu.raw_host(t).copy() for t in (P, Qo, R)]
+
+    first = run()
+    if twice:   # run-to-run determinism: identical bits
+        for a, b in zip(first, run()):
+            assert np.array_equal(a, b)
+    val = _decode_inputs(inp, dtype)
+    got = [gu.to_host(t, out_dtype) for t in (P, Qo, R)]
+    if samples is None:
+        ref = [om.forward(val["X"], val["W"], 8), om.backward_dx(val["dY"], val["W"], 8),
+               om.backward_dw(val["X"], val["dY"], 8)]
+        for g, r, name in zip(got, ref, "PQR"):
+            _check(g, numfmt.round_to(r, out_dtype) if exact else r, dtype, exact, "rank share " + name)
+    else:
+        rng = np.random.default_rng(seed)
+        for g, fn, a, b, name in ((got[0], om.forward_at, val["X"], val["W"], "P"),
+                                  (got[1], om.backward_dx_at, val["dY"], val["W"], "Q"),
+                                  (got[2], om.backward_dw_at, val["X"], val["dY"], "R")):
+            rows = rng.integers(0, g.shape[0], samples)
+            cols = rng.integers(0, g.shape[1], samples)
+            # always include the corners and tile-boundary neighbours
+            rows[:4] = [0, 0, g.shape[0] - 1, g.shape[0] - 1]
+            cols[:4] = [0, g.shape[1] - 1, 0, g.shape[1] - 1]
+            r = fn(a, b, rows, cols)
+            _check(g[rows, cols], numfmt.round_to(r, out_dtype) if exact else r, dtype, exact,
+                   "rank share (sampled) " + name)
+        for g in got:   # property that holds at any size: no element left unwritten / non-finite
+            assert np.all(np.isfinite(g))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "fp8_e4m3"])
+@pytest.mark.parametrize("dist,seed", [("normal", 21), ("int", 121)])
+def test_rank_share_ragged(dtype, dist, seed):
+    # Mb=200, Kb=72, Nb=136: spans several 64-tiles with tails in every dimension
+    run_rank_share(1, 200, 72, 136, dtype, dist, seed, (0, 0, 0), twice=True)
+    run_rank_share(2, 400, 144, 272, dtype, dist, seed, (1, 0, 1), out_dtype="bf16")
+
+
+# ---- config 2: q=4, h=2048 MLP up-projection, one processor, bf16 ------------------------------
+@pytest.mark.parametrize("dist,seed", [("normal", 2), ("int", 102)])
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_config2_rank_share_bf16(dist, seed, out_dtype):
+    run_rank_share(4, 8192, 2048, 8192, "bf16", dist, seed, (1, 2, 3), out_dtype=out_dtype, twice=True)
+
+
+# ---- config 4: q=4, h=8192 MLP up-projection, one processor, bf16 (sampled) -------------------
+@pytest.mark.parametrize("dist,seed", [("normal", 4), ("int", 104)])
+def test_config4_rank_share_bf16(dist, seed):
+    run_rank_share(4, 32768, 8192, 32768, "bf16", dist, seed, (1, 2, 3), out_dtype="bf16", samples=4096,
+                   twice=(dist == "int"))
+
+
+# ---- config 5: q=8, h=12288 MLP up-projection, one processor, fp8 e4m3 with per-tensor scales --
+@pytest.mark.parametrize("dist,seed", [("normal", 5), ("int", 105)])
+def test_config5_rank_share_fp8(dist, seed):
+    run_rank_share(8, 16384, 12288, 49152, "fp8_e4m3", dist, seed, (1, 2, 3), out_dtype="bf16", samples=4096)
+
+
+# ---- config 3: the four linears of one Transformer layer on the 64-processor virtual cube ------
+def run_virtual_cube_sampled(q, M, K, N, dtype, dist, seed, ax, samples=2048):
+    """Full-size virtual cube; the oracle evaluates sampled entries of the final Y, dX, dW and of
+    one processor's partial products."""
+    exact = dist == "int"
+    inp = synth.linear_inputs(M, K, N, dtype, dist, seed)
+    val = _decode_inputs(inp, dtype)
+    cube = Cube(q, M, K, N, ax)
+    d = _desc(q, M, K, N, dtype, "f32", "bf16", ax, inp)
+    out_axis = c3.AXIS_Z if ax == "y" else c3.AXIS_Y
+    n = q ** 3
+    dev = {k: gu.to_device(raw) for k, (raw, _) in inp.items()}
+    xs, ws, gs = gu.empty((n, cube.Ms, cube.Kb), dtype), gu.empty((n, cube.Kb, cube.Ns), dtype), \
+        gu.empty((n, cube.Ms, cube.Nb), dtype)
+    c3.virtual_cube_scatter(d, c3.OPERAND_X, dev["X"], xs)
+    c3.virtual_cube_scatter(d, c3.OPERAND_W, dev["W"], ws)
+    c3.virtual_cube_scatter(d, c3.OPERAND_DY, dev["dY"], gs)
+    xb, wb, gb = gu.empty((n, cube.Mb, cube.Kb), dtype), gu.empty((n, cube.Kb, cube.Nb), dtype), \
+        gu.empty((n, cube.Mb, cube.Nb), dtype)
+    c3.virtual_cube_gather(d, c3.OPERAND_X, AX[ax], xs, xb)
+    c3.virtual_cube_gather(d, c3.OPERAND_W, c3.AXIS_X, ws, wb)
+    c3.virtual_cube_gather(d, c3.OPERAND_DY, out_axis, gs, gb)
+    assert np.array_equal(gu.raw_host(xb).reshape(q, q, q, cube.Mb, cube.Kb), cube.block_x(inp["X"][0]))
+    assert np.array_equal(gu.raw_host(wb).reshape(q, q, q, cube.Kb, cube.Nb), cube.block_w(inp["W"][0]))
+    assert np.array_equal(gu.raw_host(gb).reshape(q, q, q, cube.Mb, cube.Nb), cube.block_y(inp["dY"][0]))
+    rng = np.random.default_rng(seed)
+    finals = []
+    for op, which, axis, a, b, fn, fa, fb, rows_cols, blk in (
+            (c3.cube3d_linear_fwd, c3.OPERAND_Y, out_axis, xb, wb, om.forward_at, "X", "W", (M, N),
+             (cube.Mb, cube.Nb)),
+            (c3.cube3d_linear_bwd_dx, c3.OPERAND_DX, AX[ax], gb, wb, om.backward_dx_at, "dY", "W", (M, K),
+             (cube.Mb, cube.Kb)),
+            (c3.cube3d_linear_bwd_dw, c3.OPERAND_DW, c3.AXIS_X, xb, gb, om.backward_dw_at, "X", "dY", (K, N),
+             (cube.Kb, cube.Nb))):
+        opcode = {c3.OPERAND_Y: c3.OP_FWD, c3.OPERAND_DX: c3.OP_BWD_DX, c3.OPERAND_DW: c3.OP_BWD_DW}[which]
+        part = gu.empty((n,) + blk, "f32")
+        op(d, c3.ALL_RANKS, a, b, part, gu.workspace(d, opcode, True))
+        shard_shape = {c3.OPERAND_Y: (cube.Ms, cube.Nb), c3.OPERAND_DX: (cube.Ms, cube.Kb),
+                       c3.OPERAND_DW: (cube.Kb, cube.Ns)}[which]
+        sh = gu.empty((n,) + shard_shape, "bf16")
+        c3.virtual_cube_reduce_scatter(d, which, axis, part, sh)
+        full = gu.empty(rows_cols, "bf16")
+        c3.virtual_cube_assemble(d, which, sh, full)
+        torch.cuda.synchronize()
+        # one processor's partial product, sampled
+        r = tuple(int(v) for v in rng.integers(0, q, 3))
+        ridx = (r[0] * q + r[1]) * q + r[2]
+        ph = part[ridx].cpu().numpy().astype(np.float64)
+        rr, cc = rng.integers(0, blk[0], samples), rng.integers(0, blk[1], samples)
+        blocks = {"X": cube.x_block_slice, "W": cube.w_block_slice, "dY": cube.y_block_slice}
+        ref = fn(val[fa][blocks[fa](*r)], val[fb][blocks[fb](*r)], rr, cc)
+        _check(ph[rr, cc], numfmt.round_to(ref, "f32") if exact else ref, dtype, exact, "partial (sampled)")
+        del part, ph
+        # the assembled result, sampled
+        fh = gu.to_host(full, "bf16")
+        rr, cc = rng.integers(0, rows_cols[0], samples), rng.integers(0, rows_cols[1], samples)
+        ref = fn(val[fa], val[fb], rr, cc)
+        _check(fh[rr, cc], numfmt.round_to(ref, "bf16") if exact else ref, dtype, exact, "assembled (sampled)")
+        assert np.all(np.isfinite(fh))
+        finals.append(full)
+    return finals
+
+
+CONFIG3 = [("qkv", 2048, 6144, "y", 31), ("attn_out", 2048, 2048, "z", 32),
+           ("mlp_up", 2048, 8192, "y", 33), ("mlp_down", 8192, 2048, "z", 34)]
+
+
+@pytest.mark.parametrize("name,K,N,ax,seed", CONFIG3)
+@pytest.mark.parametrize("dist", ["normal", "int"])
+def test_config3_virtual_cube_bf16(name, K, N, ax, seed, dist):
+    run_virtual_cube_sampled(4, 8192, K, N, "bf16", dist, seed + (100 if dist == "int" else 0), ax)
