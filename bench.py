@@ -1,0 +1,338 @@
+#!/usr/bin/env python3
+"""Benchmark of the 3-D linear layer's per-rank hot path on one MI355X.
+
+A step is one pass of the hot path over one batch of synthetic input that is
+already resident in HBM: the forward product P = X_il W_lj and the two backward
+products Q = dY_ij W_lj^T and R = X_il^T dY_ij of one processor of the q^3 cube
+(Algorithm 1 step 3, Algorithm 2 lines 1-2).  The headline workload is the
+MFMA-bound configuration (q = 4, hidden 8192 MLP up-projection, one processor's
+share at its real shape); the other configurations are reported beside it.
+
+Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused:
+this build runs on one GPU.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "fp8_e4m3": 5000.0, "f32": 157.3}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+# name -> (q, M, K, N, in dtype, out dtype of the partial products, description)
+RANK_SHARE = {
+    "config2": (4, 8192, 2048, 8192, "bf16", "bf16",
+                "one rank's share, q=4, MLP up-proj h=2048->8192, tokens 8192: X_il [2048,512] W_lj [512,2048] "
+                "dY_ij [2048,2048], bf16 in, fp32 accumulate, bf16 out"),
+    "config4": (4, 32768, 8192, 32768, "bf16", "bf16",
+                "one rank's share, q=4, MLP up-proj h=8192->32768, tokens 32768: X_il [8192,2048] W_lj [2048,8192] "
+                "dY_ij [8192,8192], bf16 in, fp32 accumulate, bf16 out"),
+    "config5": (8, 16384, 12288, 49152, "fp8_e4m3", "bf16",
+                "one rank's share, q=8, MLP up-proj h=12288->49152, tokens 16384: X_il [2048,1536] W_lj [1536,6144] "
+                "dY_ij [2048,6144], fp8 e4m3 in with per-tensor scales, fp32 accumulate, bf16 out"),
+}
+CONFIG3 = [("qkv", 2048, 6144, "y"), ("attn_out", 2048, 2048, "z"), ("mlp_up", 2048, 8192, "y"),
+           ("mlp_down", 8192, 2048, "z")]
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="config4", choices=sorted(RANK_SHARE))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time aimed at by the cpu_baseline sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference for scaling profiler byte counters)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2105_14450_amd as c3
+    from paper_2105_14450_amd import synth
+    if not os.path.exists(c3.binding.LIB_PATH):
+        from paper_2105_14450_amd import build as _b
+        _b.build()
+    c3.binding.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    store = {"f32": torch.float32, "bf16": torch.int16, "fp8_e4m3": torch.uint8}
+
+    def dev(raw):
+        raw = np.ascontiguousarray(raw)
+        if raw.dtype == np.uint16:
+            raw = raw.view(np.int16)
+        return torch.from_numpy(raw).cuda()
+
+    def timed(fn, iters):
+        """Average milliseconds of fn() over `iters` back-to-back calls (HIP events on the launch stream)."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def timed_graph(fn, iters):
+        """Same, with the `iters` launches replayed from one HIP graph (no host launch gaps)."""
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(iters):
+                    fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        g.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def rank_share(name, seed):
+        q, M, K, N, dt, odt, desc = RANK_SHARE[name]
+        Mb, Kb, Nb = M // q, K // q, N // q
+        X = synth.store(synth.draw((Mb, Kb), "normal", seed, synth.TID_X), dt)
+        W = synth.store(synth.draw((Kb, Nb), "normal", seed, synth.TID_W, 0.02), dt)
+        G = synth.store(synth.draw((Mb, Nb), "normal", seed, synth.TID_DY), dt)
+        d = c3.make_desc(q, M, K, N, in_dtype=c3.binding.DTYPE_CODES[dt], out_dtype=c3.binding.DTYPE_CODES[odt],
+                         scale_x=X[1], scale_w=W[1], scale_dy=G[1])
+        t = {"X": dev(X[0]), "W": dev(W[0]), "G": dev(G[0]),
+             "P": torch.empty((Mb, Nb), dtype=store[odt], device="cuda"),
+             "Q": torch.empty((Mb, Kb), dtype=store[odt], device="cuda"),
+             "R": torch.empty((Kb, Nb), dtype=store[odt], device="cuda")}
+        ws = {}
+        for op in (c3.OP_FWD, c3.OP_BWD_DX, c3.OP_BWD_DW):
+            n = c3.cube3d_workspace_bytes(d, op, False)
+            ws[op] = torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+        rank = (1, 2, 3)
+        ops = {
+            "fwd": lambda: c3.cube3d_linear_fwd(d, rank, t["X"], t["W"], t["P"], ws[c3.OP_FWD]),
+            "bwd_dx": lambda: c3.cube3d_linear_bwd_dx(d, rank, t["G"], t["W"], t["Q"], ws[c3.OP_BWD_DX]),
+            "bwd_dw": lambda: c3.cube3d_linear_bwd_dw(d, rank, t["X"], t["G"], t["R"], ws[c3.OP_BWD_DW]),
+        }
+        flop = 2.0 * Mb * Kb * Nb
+        host = {"X": X, "W": W, "G": G}
+        return ops, flop, (Mb, Kb, Nb), desc, dt, host
+
+    # ---- headline workload ------------------------------------------------------------------------
+    ops, flop, (Mb, Kb, Nb), desc, dt, host = rank_share(args.workload, {"config2": 2, "config4": 4, "config5": 5}[args.workload])
+
+    def step():
+        ops["fwd"]()
+        ops["bwd_dx"]()
+        ops["bwd_dw"]()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    value = 3.0 * flop / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel launch durations, measured live (same stream, HIP events)
+    kern = {}
+    small = flop < 5e10
+    for name, fn in ops.items():
+        ms = timed_graph(fn, 50) if small else timed(fn, max(20, args.steps // 4))
+        kern[name] = {"avg_us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
+                      "frac_of_peak": round(flop / (ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 4)}
+    dom = max(kern, key=lambda k: kern[k]["avg_us"])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dom)
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": kern[dom]["tflops"], "peak": PEAK_TFLOPS[dt],
+                "unit": "TFLOP/s", "frac": kern[dom]["frac_of_peak"], "traffic": traffic,
+                "flop_per_launch": flop, "avg_launch_us": kern[dom]["avg_us"]}
+
+    out = {
+        "metric": "per-rank 3-D linear fwd+bwd TFLOP/s (bf16)" if dt == "bf16" else
+                  "per-rank 3-D linear fwd+bwd TFLOP/s (%s)" % dt,
+        "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "fp8_e4m3": "fp8", "f32": "f32"}[dt], "data": "synthetic",
+        "config": {"workload": args.workload + ": " + desc, "rank_block": [Mb, Kb, Nb],
+                   "step": "fwd + bwd_dx + bwd_dw, 3 launches", "frac_of_bf16_peak": round(value / PEAK_TFLOPS["bf16"], 4)},
+        "roofline": roofline,
+        "kernels": kern,
+    }
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    # ---- the other configurations (short runs) ------------------------------------------------------
+    if not args.no_extra:
+        extra = {}
+        for name in sorted(RANK_SHARE):
+            if name == args.workload:
+                continue
+            try:
+                o, f, blk, _, d2, _h = rank_share(name, {"config2": 2, "config4": 4, "config5": 5}[name])
+                r = {}
+                for k, fn in o.items():
+                    ms = timed_graph(fn, 50) if f < 5e10 else timed(fn, 20)
+                    r[k] = {"avg_us": round(ms * 1e3, 2), "tflops": round(f / (ms * 1e-3) / 1e12, 1)}
+                r["fwd_bwd_tflops"] = round(3 * f / sum(v["avg_us"] for v in r.values()) / 1e6, 1)
+                r["frac_of_bf16_peak"] = round(r["fwd_bwd_tflops"] / PEAK_TFLOPS["bf16"], 4)
+                r["dtype"] = d2
+                extra[name] = r
+                del o, _h
+                torch.cuda.empty_cache()
+            except Exception as exc:   # a failed side run must not lose the headline line
+                extra[name] = {"error": repr(exc)}
+        try:
+            extra["config3"] = bench_virtual_cube(c3, synth, torch, np, timed)
+        except Exception as exc:
+            extra["config3"] = {"error": repr(exc)}
+        out["per_config"] = extra
+
+    # ---- the oracle on the host cores, bounded sample -------------------------------------------------
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(host, dt, args.cpu_seconds)
+
+    print(json.dumps(out))
+    return 0
+
+
+def bench_virtual_cube(c3, synth, torch, np, timed):
+    """Config 3: the four linears of one Transformer layer on the 64-processor virtual cube (q = 4,
+    8192 tokens, bf16): batched products over all ranks plus the on-HBM gathers and reduce-scatters."""
+    q, M = 4, 8192
+    n = q ** 3
+    res = {}
+    tot_flop, tot_ms = 0.0, 0.0
+    for name, K, N, ax in CONFIG3:
+        in_axis = c3.AXIS_Y if ax == "y" else c3.AXIS_Z
+        out_axis = c3.AXIS_Z if ax == "y" else c3.AXIS_Y
+        d = c3.make_desc(q, M, K, N, in_dtype=c3.BF16, out_dtype=c3.F32, shard_dtype=c3.BF16, in_axis=in_axis)
+        Mb, Kb, Nb, Ms, Ns = M // q, K // q, N // q, M // q ** 2, N // q ** 2
+        i16, f32 = torch.int16, torch.float32
+        g = torch.Generator(device="cuda").manual_seed(31)
+        mk = lambda shape, s: (torch.randn(shape, device="cuda", generator=g) * s).to(torch.bfloat16).view(i16)
+        xs, ws, gs = mk((n, Ms, Kb), 1.0), mk((n, Kb, Ns), 0.02), mk((n, Ms, Nb), 1.0)
+        xb = torch.empty((n, Mb, Kb), dtype=i16, device="cuda")
+        wb = torch.empty((n, Kb, Nb), dtype=i16, device="cuda")
+        gb = torch.empty((n, Mb, Nb), dtype=i16, device="cuda")
+        big = max(Mb * Nb, Mb * Kb, Kb * Nb)
+        buf = torch.empty((n * big,), dtype=f32, device="cuda")   # partial products of all three passes
+        P = buf[: n * Mb * Nb].view(n, Mb, Nb)
+        ysh = torch.empty((n, Ms, Nb), dtype=i16, device="cuda")
+        wsb = {}
+        for op in (c3.OP_FWD, c3.OP_BWD_DX, c3.OP_BWD_DW):
+            nb = c3.cube3d_workspace_bytes(d, op, True)
+            wsb[op] = torch.empty(nb, dtype=torch.uint8, device="cuda") if nb else None
+        r = {}
+        flop = 2.0 * Mb * Kb * Nb * n
+        steps = {
+            "gather_x": (lambda: c3.virtual_cube_gather(d, c3.OPERAND_X, in_axis, xs, xb), (1 + q) * xs.numel() * 2),
+            "gather_w": (lambda: c3.virtual_cube_gather(d, c3.OPERAND_W, c3.AXIS_X, ws, wb), (1 + q) * ws.numel() * 2),
+            "gather_dy": (lambda: c3.virtual_cube_gather(d, c3.OPERAND_DY, out_axis, gs, gb), (1 + q) * gs.numel() * 2),
+            "fwd": (lambda: c3.cube3d_linear_fwd(d, c3.ALL_RANKS, xb, wb, P, wsb[c3.OP_FWD]), None),
+            "reduce_scatter_y": (lambda: c3.virtual_cube_reduce_scatter(d, c3.OPERAND_Y, out_axis, P, ysh),
+                                 P.numel() * 4 + ysh.numel() * 2),
+        }
+        for k, (fn, nbytes) in steps.items():
+            fn()
+            ms = timed(fn, 10)
+            if nbytes is None:
+                r[k] = {"avg_us": round(ms * 1e3, 1), "tflops": round(flop / (ms * 1e-3) / 1e12, 1)}
+                tot_flop += flop
+                tot_ms += ms
+            else:
+                r[k] = {"avg_us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                        "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
+        Qv = buf[: n * Mb * Kb].view(n, Mb, Kb)
+        Rv = buf[: n * Kb * Nb].view(n, Kb, Nb)
+        for k, fn in (("bwd_dx", lambda: c3.cube3d_linear_bwd_dx(d, c3.ALL_RANKS, gb, wb, Qv, wsb[c3.OP_BWD_DX])),
+                      ("bwd_dw", lambda: c3.cube3d_linear_bwd_dw(d, c3.ALL_RANKS, xb, gb, Rv, wsb[c3.OP_BWD_DW]))):
+            fn()
+            ms = timed(fn, 10)
+            r[k] = {"avg_us": round(ms * 1e3, 1), "tflops": round(flop / (ms * 1e-3) / 1e12, 1)}
+            tot_flop += flop
+            tot_ms += ms
+        res[name] = r
+        del xs, ws, gs, xb, wb, gb, P, ysh, Qv, Rv, buf
+        torch.cuda.empty_cache()
+    res["products_tflops"] = round(tot_flop / (tot_ms * 1e-3) / 1e12, 1)
+    res["frac_of_bf16_peak"] = round(res["products_tflops"] / PEAK_TFLOPS["bf16"], 4)
+    return res
+
+
+def cpu_baseline(host, dt, seconds):
+    """Time the CPU oracle, as it stands, on a slab of the same workload: the first `rows` rows of
+    the forward and dX outputs and the first `rows_w` rows of dW, sized from a short calibration
+    run so that the whole sample takes about `seconds` of wall time (at most the full step)."""
+    import numpy as np
+
+    from oracle import matmul as om
+    from oracle import numfmt
+    X = numfmt.decode(host["X"][0], dt, host["X"][1])
+    W = numfmt.decode(host["W"][0], dt, host["W"][1])
+    G = numfmt.decode(host["G"][0], dt, host["G"][1])
+    threads = om.max_threads()
+    try:
+        threads = min(threads, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        pass
+    Mb, Kb = X.shape
+    Nb = W.shape[1]
+    t0 = time.time()
+    om.forward(X[:64], W, threads)
+    rate = 2.0 * 64 * Kb * Nb / max(time.time() - t0, 1e-6)          # flop/s, calibration only
+    step_flop = 3 * 2.0 * Mb * Kb * Nb
+    frac = min(1.0, rate * seconds / step_flop)
+    rows = max(64, min(Mb, int(Mb * frac)))
+    rows_w = max(8, min(Kb, int(Kb * frac)))
+    t0 = time.time()
+    om.forward(X[:rows], W, threads)
+    om.backward_dx(G[:rows], W, threads)
+    om.backward_dw(np.ascontiguousarray(X[:, :rows_w]), G, threads)
+    dt_s = time.time() - t0
+    flop = 2.0 * rows * Kb * Nb * 2 + 2.0 * Mb * rows_w * Nb
+    return {"value": round(flop / dt_s / 1e12, 6), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "seconds": round(dt_s, 2),
+            "sample": "fp64 triple-loop oracle on the same inputs: rows [0,%d) of the forward and dX outputs and "
+                      "rows [0,%d) of dW (%.1f GFLOP of the step's %.1f)" % (rows, rows_w, flop / 1e9,
+                                                                             step_flop / 1e9)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

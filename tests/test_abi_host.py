@@ -1,0 +1,132 @@
+"""Host-side tests of the C ABI: the library loads, exports every symbol the header declares,
+and every argument error is reported before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2105_14450_amd as c3
+from paper_2105_14450_amd.binding import Desc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(c3.binding.LIB_PATH):
+        from paper_2105_14450_amd import build
+        build.build()
+    return c3.binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "cube3d.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b((?:cube3d|virtual_cube)_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(c3.binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert c3.cube3d_version() == 100
+
+
+def test_desc_mirror_matches_the_header_layout():
+    # int32 q, in_axis; int64 M, K, N; int32 in/out/shard dtype; float x3
+    assert ctypes.sizeof(Desc) == 56
+    assert Desc.M.offset == 8 and Desc.in_dtype.offset == 32 and Desc.scale_x.offset == 44
+
+
+FAKE = ctypes.c_void_p(0x10000)          # aligned, never dereferenced: validation fails first
+ODD = ctypes.c_void_p(0x10008)
+
+
+def good(**kw):
+    args = dict(q=2, M=256, K=128, N=128, in_dtype=c3.F32, out_dtype=c3.F32, shard_dtype=c3.F32)
+    args.update(kw)
+    return c3.make_desc(**args)
+
+
+def fwd(lib, d, rank=(0, 0, 0), a=FAKE, b=FAKE, c=FAKE, ws=None, ws_bytes=0):
+    dp = ctypes.byref(d) if d is not None else None
+    return lib.cube3d_linear_fwd(dp, rank[0], rank[1], rank[2], a, b, c, ws, ws_bytes, None)
+
+
+def test_descriptor_errors(lib):
+    assert fwd(lib, None) == c3.EINVAL
+    assert fwd(lib, good(q=0)) == c3.EINVAL
+    assert fwd(lib, good(q=-3)) == c3.EINVAL
+    assert fwd(lib, good(in_axis=c3.AXIS_X)) == c3.EINVAL
+    assert fwd(lib, good(in_axis=7)) == c3.EINVAL
+    assert fwd(lib, good(M=258)) == c3.ESHAPE       # q^2 does not divide M
+    assert fwd(lib, good(N=130)) == c3.ESHAPE
+    assert fwd(lib, good(K=127)) == c3.ESHAPE       # q does not divide K
+    assert fwd(lib, good(M=0)) == c3.ESHAPE
+    assert fwd(lib, good(K=-128)) == c3.ESHAPE
+    assert fwd(lib, good(q=64, M=64 * 64, K=64, N=64 * 64)) == c3.ESHAPE   # cube too large for one launch
+    assert fwd(lib, good(in_dtype=9)) == c3.EDTYPE
+    assert fwd(lib, good(out_dtype=c3.FP8_E4M3)) == c3.EDTYPE
+    assert fwd(lib, good(shard_dtype=5)) == c3.EDTYPE
+    assert fwd(lib, good(in_dtype=c3.FP8_E4M3, scale_x=0.0)) == c3.EINVAL
+    assert fwd(lib, good(in_dtype=c3.FP8_E4M3, scale_w=-1.0)) == c3.EINVAL
+    assert fwd(lib, good(in_dtype=c3.FP8_E4M3, scale_dy=float("nan"))) == c3.EINVAL
+
+
+def test_rank_and_pointer_errors(lib):
+    d = good()
+    for rank in ((2, 0, 0), (0, -2, 0), (0, 0, 5), (-1, 0, 0), (-1, -1, 0)):
+        assert fwd(lib, d, rank) == c3.EINVAL
+    assert fwd(lib, d, a=None) == c3.EINVAL
+    assert fwd(lib, d, b=None) == c3.EINVAL
+    assert fwd(lib, d, c=None) == c3.EINVAL
+    assert fwd(lib, d, a=ODD) == c3.EINVAL
+    assert fwd(lib, d, c=ODD) == c3.EINVAL
+    for f in (lib.cube3d_linear_bwd_dx, lib.cube3d_linear_bwd_dw):
+        assert f(ctypes.byref(d), 0, 0, 0, None, FAKE, FAKE, None, 0, None) == c3.EINVAL
+        assert f(ctypes.byref(good(M=6)), 0, 0, 0, FAKE, FAKE, FAKE, None, 0, None) == c3.ESHAPE
+
+
+def test_collective_argument_errors(lib):
+    d = good()                       # in_axis = Y, so the output direction is Z
+    g = lib.virtual_cube_gather
+    assert g(ctypes.byref(d), c3.OPERAND_X, c3.AXIS_Z, FAKE, FAKE, None) == c3.EINVAL
+    assert g(ctypes.byref(d), c3.OPERAND_W, c3.AXIS_Y, FAKE, FAKE, None) == c3.EINVAL
+    assert g(ctypes.byref(d), c3.OPERAND_DY, c3.AXIS_Y, FAKE, FAKE, None) == c3.EINVAL
+    assert g(ctypes.byref(d), c3.OPERAND_Y, c3.AXIS_Z, FAKE, FAKE, None) == c3.EINVAL     # not a gather operand
+    assert g(ctypes.byref(d), c3.OPERAND_X, c3.AXIS_Y, None, FAKE, None) == c3.EINVAL
+    assert g(ctypes.byref(d), c3.OPERAND_X, c3.AXIS_Y, FAKE, ODD, None) == c3.EINVAL
+    assert g(None, c3.OPERAND_X, c3.AXIS_Y, FAKE, FAKE, None) == c3.EINVAL
+    r = lib.virtual_cube_reduce_scatter
+    assert r(ctypes.byref(d), c3.OPERAND_Y, c3.AXIS_Y, FAKE, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(d), c3.OPERAND_DX, c3.AXIS_Z, FAKE, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(d), c3.OPERAND_DW, c3.AXIS_Z, FAKE, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(d), c3.OPERAND_X, c3.AXIS_Y, FAKE, FAKE, None) == c3.EINVAL     # not a reduce operand
+    assert r(ctypes.byref(d), c3.OPERAND_Y, c3.AXIS_Z, FAKE, None, None) == c3.EINVAL
+    dz = good(in_axis=c3.AXIS_Z)     # exchanged directions: X travels along z, Y along y
+    assert g(ctypes.byref(dz), c3.OPERAND_X, c3.AXIS_Y, FAKE, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(dz), c3.OPERAND_Y, c3.AXIS_Z, FAKE, FAKE, None) == c3.EINVAL
+    for f in (lib.virtual_cube_scatter, lib.virtual_cube_assemble):
+        assert f(ctypes.byref(d), 17, FAKE, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(d), c3.OPERAND_X, None, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(good(N=6)), c3.OPERAND_X, FAKE, FAKE, None) == c3.ESHAPE
+
+
+def test_workspace_query_and_strings(lib):
+    assert c3.cube3d_workspace_bytes(good(M=7), c3.OP_FWD, False) == 0
+    assert c3.cube3d_workspace_bytes(good(), 42, False) == 0
+    assert isinstance(c3.cube3d_workspace_bytes(good(), c3.OP_FWD, True), int)
+    seen = set()
+    for code in (c3.OK, c3.EINVAL, c3.ESHAPE, c3.EDTYPE, c3.EWORKSPACE, c3.ELAUNCH, c3.ENOTIMPL, -99):
+        s = c3.status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    with pytest.raises(c3.binding.Cube3DError) as e:
+        c3.binding._check(c3.ESHAPE, "where")
+    assert e.value.status == c3.ESHAPE
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    d = good()
+    t = torch.zeros(4)
+    with pytest.raises(ValueError):
+        c3.cube3d_linear_fwd(d, (0, 0, 0), t, t, t)
