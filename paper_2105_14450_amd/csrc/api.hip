@@ -99,8 +99,7 @@ int build_gemm(const cube3d_desc *d, int op, int batch, const void *A, const voi
 
 size_t workspace_for(const GemmArgs &a)
 {
-    if (a.in_dtype == CUBE3D_BF16) return gemm_bf16_fast_workspace(a);
-    return 0;
+    return gemm_fast_workspace(a);
 }
 
 int run_product(const cube3d_desc *d, int op, int i, int j, int l, const void *A, const void *B, void *C, void *ws,
@@ -117,13 +116,8 @@ int run_product(const cube3d_desc *d, int op, int i, int j, int l, const void *A
     if (rc != CUBE3D_OK) return rc;
     const size_t need = workspace_for(a);
     if (need > 0 && (!ws || ws_bytes < need)) return CUBE3D_EWORKSPACE;
-    if (a.in_dtype == CUBE3D_BF16) {
-        rc = gemm_bf16_fast(a);
-        if (rc != CUBE3D_ENOTIMPL) return rc;
-    } else if (a.in_dtype == CUBE3D_FP8_E4M3) {
-        rc = gemm_fp8_fast(a);
-        if (rc != CUBE3D_ENOTIMPL) return rc;
-    }
+    rc = gemm_fast(a);
+    if (rc != CUBE3D_ENOTIMPL) return rc;
     return gemm_generic(a);
 }
 

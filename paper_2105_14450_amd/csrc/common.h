@@ -41,12 +41,9 @@ struct GemmArgs {
 // Any shape, any supported dtype; bounds-checked.  Returns a cube3d_status.
 int gemm_generic(const GemmArgs &g);
 
-// Tuned bf16 path; returns CUBE3D_ENOTIMPL when the shape does not fit its tiles.
-int gemm_bf16_fast(const GemmArgs &g);
-size_t gemm_bf16_fast_workspace(const GemmArgs &g);
-
-// Tuned fp8 path; same contract.
-int gemm_fp8_fast(const GemmArgs &g);
+// Tuned bf16 / fp8 path; returns CUBE3D_ENOTIMPL when the shape does not fit its tiles.
+int gemm_fast(const GemmArgs &g);
+size_t gemm_fast_workspace(const GemmArgs &g);
 
 // Geometry of the virtual cube and the data-movement kernels over it.
 struct CubeGeom {

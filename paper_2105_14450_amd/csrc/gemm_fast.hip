@@ -1,0 +1,115 @@
+// Dispatch of the tuned MFMA product kernel (gemm_mfma_kernel.h): tile configuration per
+// shape and dtype, deterministic split-K for shapes with very few output tiles, and the
+// fixed-order reduction of the split partials.
+#include "gemm_mfma_kernel.h"
+
+namespace cube3d {
+using namespace mfk;
+
+namespace {
+
+constexpr int NUM_CU = 256;
+
+struct Plan {
+    int tile;     // 256 or 128 (square output tile); 0 = shape not supported by the tuned kernel
+    int splits;
+};
+
+// Pure function of the shape, so that cube3d_workspace_bytes() and the launch agree.
+Plan make_plan(const GemmArgs &g)
+{
+    Plan p{0, 1};
+    const bool fp8 = g.in_dtype == CUBE3D_FP8_E4M3;
+    if (g.in_dtype != CUBE3D_BF16 && !fp8) return p;
+    const int es = fp8 ? 1 : 2;
+    const int64_t align = 16 / es;              // operands are moved in 16-byte pieces
+    if (g.lda % align || g.ldb % align || g.strideA % align || g.strideB % align) return p;
+    if (g.ldc % 8 || g.strideC % 8) return p;
+    if (g.batch > 16384) return p;
+    if (g.out_dtype != CUBE3D_F32 && g.out_dtype != CUBE3D_BF16) return p;
+    const int64_t ktile = 64 / es;              // K elements per 64-byte K-tile
+    if (g.Kc % ktile || g.Kc < ktile) return p;
+    const int64_t nk = g.Kc / ktile;
+    const bool fits256 = g.Mo % 256 == 0 && g.No % 256 == 0;
+    const bool fits128 = !fp8 && g.Mo % 128 == 0 && g.No % 128 == 0;
+    if (!fits256 && !fits128) return p;
+    const int64_t tiles256 = fits256 ? (g.Mo / 256) * (g.No / 256) * g.batch : 0;
+    if (fits256 && (tiles256 >= (3 * NUM_CU) / 4 || !fits128)) p.tile = 256;
+    else p.tile = 128;
+    // Split-K only when the output tiles would leave most CUs idle; the partials cost
+    // splits * Mo * No * 4 bytes of HBM traffic each way, so keep them few and small.
+    const int64_t tiles = (g.Mo / p.tile) * (g.No / p.tile) * g.batch;
+    int splits = 1;
+    while (tiles * splits * 2 <= NUM_CU / 2 && splits < 16 && nk % (splits * 2) == 0 && nk / (splits * 2) >= 16 &&
+           (int64_t)splits * 2 * g.Mo * g.No * g.batch * 4 <= (32ll << 20))
+        splits *= 2;
+    if ((int64_t)g.batch * splits > 65535) splits = 1;
+    p.splits = splits;
+    return p;
+}
+
+// out[b][m][n] = sum over s (ascending) of ws[b][s][m][n], rounded once to the output type.
+template <typename TOut>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, TOut *__restrict__ out,
+                                                           int splits, int64_t mn, int64_t ldc, int64_t No,
+                                                           int64_t sC)
+{
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= mn) return;
+    const int b = blockIdx.y;
+    const float *src = ws + (int64_t)b * splits * mn + e;
+    f32x4 acc = *reinterpret_cast<const f32x4 *>(src);
+    for (int s = 1; s < splits; ++s) {
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(src + s * mn);
+        acc += v;
+    }
+    const int64_t row = e / No, col = e - row * No;
+    TOut *dst = out + b * sC + row * ldc + col;
+    if (sizeof(TOut) == 4) {
+        *reinterpret_cast<f32x4 *>(dst) = acc;
+    } else {
+        uint2 v;
+        v.x = (unsigned)f32_to_bf16_bits(acc[0]) | ((unsigned)f32_to_bf16_bits(acc[1]) << 16);
+        v.y = (unsigned)f32_to_bf16_bits(acc[2]) | ((unsigned)f32_to_bf16_bits(acc[3]) << 16);
+        *reinterpret_cast<uint2 *>(dst) = v;
+    }
+}
+
+template <typename E, int T, typename TOut> int run_tile(const GemmArgs &g, const Plan &pl)
+{
+    constexpr int BKB = 64, NSTAGE = 4;
+    if (pl.splits == 1) return launch_layout<E, T, T, BKB, NSTAGE, TOut>(g, 1, g.C, g.ldc, g.strideC, 0, g.alpha);
+    // the scale is applied once, to the partials (alpha * sum = sum of alpha * parts only up to
+    // rounding, so apply it before the fixed-order sum on every run alike)
+    const int64_t mn = g.Mo * g.No;
+    int rc = launch_layout<E, T, T, BKB, NSTAGE, float>(g, pl.splits, g.workspace, g.No, (int64_t)pl.splits * mn, mn,
+                                                        g.alpha);
+    if (rc != CUBE3D_OK) return rc;
+    dim3 grid((unsigned)((mn / 4 + 255) / 256), (unsigned)g.batch, 1);
+    hipLaunchKernelGGL((splitk_reduce_kernel<TOut>), grid, dim3(256), 0, g.stream,
+                       static_cast<const float *>(g.workspace), static_cast<TOut *>(g.C), pl.splits, mn, g.ldc, g.No,
+                       g.strideC);
+    return launch_status();
+}
+
+}  // namespace
+
+size_t gemm_fast_workspace(const GemmArgs &g)
+{
+    const Plan pl = make_plan(g);
+    if (pl.tile == 0 || pl.splits == 1) return 0;
+    return (size_t)g.batch * pl.splits * g.Mo * g.No * sizeof(float);
+}
+
+int gemm_fast(const GemmArgs &g)
+{
+    const Plan pl = make_plan(g);
+    if (pl.tile == 0) return CUBE3D_ENOTIMPL;
+    const bool f32 = g.out_dtype == CUBE3D_F32;
+    if (g.in_dtype == CUBE3D_FP8_E4M3)
+        return f32 ? run_tile<Fp8, 256, float>(g, pl) : run_tile<Fp8, 256, unsigned short>(g, pl);
+    if (pl.tile == 256) return f32 ? run_tile<Bf16, 256, float>(g, pl) : run_tile<Bf16, 256, unsigned short>(g, pl);
+    return f32 ? run_tile<Bf16, 128, float>(g, pl) : run_tile<Bf16, 128, unsigned short>(g, pl);
+}
+
+}  // namespace cube3d

@@ -216,6 +216,16 @@ def test_rank_share_ragged(dtype, dist, seed):
     run_rank_share(2, 400, 144, 272, dtype, dist, seed, (1, 0, 1), out_dtype="bf16")
 
 
+# ---- tile-aligned small shapes: 128x128 tiles, split-K with the fixed-order reduction -----------
+@pytest.mark.parametrize("M,K,N", [(256, 4096, 384), (512, 512, 512), (128, 8192, 128), (384, 1024, 2048),
+                                   (256, 8192, 256), (768, 320, 512)])
+@pytest.mark.parametrize("dist,seed", [("normal", 41), ("int", 141)])
+@pytest.mark.parametrize("dtype,out_dtype", [("bf16", "f32"), ("bf16", "bf16"), ("fp8_e4m3", "f32"),
+                                             ("fp8_e4m3", "bf16")])
+def test_rank_share_small_tiles_and_split_k(M, K, N, dist, seed, dtype, out_dtype):
+    run_rank_share(1, M, K, N, dtype, dist, seed, (0, 0, 0), out_dtype=out_dtype, twice=True)
+
+
 # ---- config 2: q=4, h=2048 MLP up-projection, one processor, bf16 ------------------------------
 @pytest.mark.parametrize("dist,seed", [("normal", 2), ("int", 102)])
 @pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
