@@ -28,7 +28,8 @@ Plan make_plan(const GemmArgs &g)
     if (g.batch > 16384) return p;
     if (g.out_dtype != CUBE3D_F32 && g.out_dtype != CUBE3D_BF16) return p;
     const int64_t ktile = 64 / es;              // K elements per 64-byte K-tile
-    if (g.Kc % ktile || g.Kc < ktile) return p;
+    // fp8: one MFMA k-step per K-tile, tiles are processed in pairs
+    if (g.Kc % (fp8 ? 2 * ktile : ktile) || g.Kc < (fp8 ? 2 * ktile : ktile)) return p;
     const int64_t nk = g.Kc / ktile;
     const bool fits256 = g.Mo % 256 == 0 && g.No % 256 == 0;
     const bool fits128 = !fp8 && g.Mo % 128 == 0 && g.No % 128 == 0;
@@ -40,7 +41,7 @@ Plan make_plan(const GemmArgs &g)
     // splits * Mo * No * 4 bytes of HBM traffic each way, so keep them few and small.
     const int64_t tiles = (g.Mo / p.tile) * (g.No / p.tile) * g.batch;
     int splits = 1;
-    while (tiles * splits * 2 <= NUM_CU / 2 && splits < 16 && nk % (splits * 2) == 0 && nk / (splits * 2) >= 16 &&
+    while (tiles * splits * 2 <= NUM_CU / 2 && splits < 16 && nk % (splits * 4) == 0 && nk / (splits * 2) >= 16 &&
            (int64_t)splits * 2 * g.Mo * g.No * g.batch * 4 <= (32ll << 20))
         splits *= 2;
     if ((int64_t)g.batch * splits > 65535) splits = 1;

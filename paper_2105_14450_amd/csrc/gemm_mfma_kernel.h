@@ -374,9 +374,10 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 __builtin_amdgcn_sched_barrier(0);
                 if (do_read) {
 #pragma unroll
-                    for (int u = (m * NR) / NM; u < ((m + 1) * NR) / NM; ++u) {
+                    for (int u = 0; u < NR; ++u) {
                         // fragments in the order the next k-step first needs them: a0 b0 a1 b1 ..., then
-                        // the rest of the longer side
+                        // the rest of the longer side; unit u goes behind MFMA (u * NM) / NR
+                        if (u < (m * NR) / NM || u >= ((m + 1) * NR) / NM) continue;
                         constexpr int TMIN = TM < TN ? TM : TN;
                         if (u < 2 * TMIN) {
                             if (u % 2 == 0) fa[cur ^ 1][u / 2] = read_a(rbase, rks, u / 2);
@@ -392,7 +393,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 if (more) {
                     const int f = ks * NM + m;
 #pragma unroll
-                    for (int idx = (f * LPT) / TOT; idx < ((f + 1) * LPT) / TOT; ++idx) {
+                    for (int idx = 0; idx < LPT; ++idx) {
+                        if (idx < (f * LPT) / TOT || idx >= ((f + 1) * LPT) / TOT) continue;
                         issue_load(idx, pre);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -407,26 +409,26 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         using F = std::false_type;
         using P0 = std::integral_constant<int, 0>;
         using P1 = std::integral_constant<int, (KS & 1)>;   // parity of the second tile of a pair
+        // Straight-line phases only: selecting an instantiation at run time inside a loop makes the
+        // register allocator spill the accumulators.
         int kt = 0;
         if (UNROLL == 2) {
+            // odd KS: the fragment buffers alternate per K-tile, so tiles go in pairs (nk is even)
+            static_assert(UNROLL == 1 || NSTAGE == 4, "the pair schedule below is written for four stages");
             for (; kt + NSTAGE < nk; kt += 2) {
                 k_tile(T{}, T{}, P0{});
                 k_tile(T{}, T{}, P1{});
             }
+            if (nk - kt == 4) {
+                k_tile(T{}, T{}, P0{});
+                k_tile(F{}, T{}, P1{});
+            }
+            k_tile(F{}, T{}, P0{});
+            k_tile(F{}, F{}, P1{});
         } else {
             for (; kt + NSTAGE - 1 < nk; ++kt) k_tile(T{}, T{}, P0{});
-        }
-        // remaining tiles one by one (at most NSTAGE of them); parity follows kt when KS is odd
-        for (; kt < nk; ++kt) {
-            const bool more = kt + NSTAGE - 1 < nk, has_next = kt + 1 < nk;
-            const bool odd = (UNROLL == 2) && (kt & 1);
-            if (more) {
-                if (odd) k_tile(T{}, T{}, P1{}); else k_tile(T{}, T{}, P0{});
-            } else if (has_next) {
-                if (odd) k_tile(F{}, T{}, P1{}); else k_tile(F{}, T{}, P0{});
-            } else {
-                if (odd) k_tile(F{}, F{}, P1{}); else k_tile(F{}, F{}, P0{});
-            }
+            for (; kt + 1 < nk; ++kt) k_tile(F{}, T{}, P0{});
+            k_tile(F{}, F{}, P0{});
         }
     }
 
