@@ -18,28 +18,30 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "
 
 
 def _compile(src):
+    """Compile one source; refuse kernels that spill registers to scratch memory (the tuned
+    kernels are sized to live in the register file: a spill is a performance bug)."""
     obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
-    subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], check=True, stderr=_filter())
+    res = subprocess.run([HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj],
+                         stderr=subprocess.PIPE, text=True)
+    name, spilled, keep = None, [], []
+    for line in res.stderr.splitlines():
+        if "kernel-resource-usage" in line:
+            if "Function Name:" in line:
+                name = line.split("Function Name:")[1].split()[0]
+            elif "ScratchSize" in line or "VGPRs Spill" in line:
+                if int(line.split(":")[-1].split()[0]) != 0:
+                    spilled.append(name)
+            continue
+        if "packed-fp32-ops" in line and "not a recognized feature" in line:
+            continue
+        keep.append(line)
+    # the remark lines come with source excerpts; print diagnostics only when the compile failed
+    if res.returncode != 0:
+        sys.stderr.write("\n".join(keep) + "\n")
+        raise subprocess.CalledProcessError(res.returncode, HIPCC)
+    if spilled:
+        raise RuntimeError("register spills in %s: %s" % (os.path.basename(src), sorted(set(spilled))))
     return obj
-
-
-class _filter:
-    """hipcc's host pass warns that it does not know the packed-fp32 feature; drop that line."""
-
-    def fileno(self):
-        return self._w
-
-    def __init__(self):
-        self._r, self._w = os.pipe()
-        import threading
-        threading.Thread(target=self._pump, daemon=True).start()
-
-    def _pump(self):
-        with os.fdopen(self._r, "r", errors="replace") as f:
-            for line in f:
-                if "packed-fp32-ops" in line and "not a recognized feature" in line:
-                    continue
-                sys.stderr.write(line)
 
 
 def sources():

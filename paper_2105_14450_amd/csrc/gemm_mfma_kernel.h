@@ -38,11 +38,19 @@ constexpr int WAVES = 4;
 // Wait until at most N of this wavefront's direct-to-LDS loads are outstanding and all of
 // its LDS reads have returned, then meet the other wavefronts.  After it, every tile whose
 // loads were waited for is visible to all wavefronts, and no wavefront still reads the stage
-// that is overwritten next.  The "memory" clobber keeps the compiler from moving LDS
-// accesses across it.
+// that is overwritten next.  The wait is the s_waitcnt builtin, not assembly text, so that the
+// compiler's own counter bookkeeping knows that no LDS read is outstanding behind it (otherwise
+// it protects reads that are long complete with waits that also cover the reads issued just
+// before, and every such wait stalls the MFMA stream).  The empty asm statements keep the
+// compiler from moving LDS accesses across the barrier.
 template <int N> __device__ __forceinline__ void tile_barrier()
 {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(N) : "memory");
+    // gfx9 encoding: vmcnt = bits 3:0 and 15:14, expcnt = bits 6:4 (7: no wait), lgkmcnt = bits 11:8
+    constexpr int imm = (N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(imm);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 // Direct-to-LDS 16-byte load: lane s of the wavefront writes LDS bytes [lds_base + 16 s, +16).
@@ -209,12 +217,20 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     constexpr int FS = (E::KSTEP * E::ELT / 2) / 16;   // 16-byte reads per K-major fragment
     static_assert(KS >= 1 && BKB % (E::KSTEP * E::ELT) == 0, "K-tile must hold whole k-steps");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wavefront tile is made of 32x32 MFMA tiles");
-    static_assert(NSTAGE >= 3, "a tile's loads are spread over a whole iteration");
+    // NSTAGE >= 3: the loads of tile kt+NSTAGE-1 are spread over the whole of iteration kt.
+    // NSTAGE == 2: the loads of tile kt+2 go into the stage of tile kt as soon as the barrier
+    // before its last k-step has shown that nobody reads it any more (all behind that k-step's MFMAs).
+    constexpr bool TWO_STAGE = NSTAGE == 2;
+    constexpr int PRE = TWO_STAGE ? 2 : NSTAGE - 1;    // tiles in flight after the prologue
+    static_assert(NSTAGE >= 2, "at least double buffering");
+    static_assert(!TWO_STAGE || KS % 2 == 0, "the two-stage schedule is written for an even number of k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
     static_assert(WAVES * EPI_BYTES <= NSTAGE * STAGE_BYTES, "epilogue staging must fit");
     static_assert((NSTAGE - 2) * LPT <= 63, "vmcnt range");
     // loads of this iteration already issued when the tile barrier (before the last k-step) is reached
     constexpr int LOADS_BEFORE_BARRIER = ((KS - 1) * NM * LPT) / TOT;
+    // loads that may still be in flight behind the steady-state barrier: those of the tiles after kt+1
+    constexpr int STEADY_VMCNT = (NSTAGE == 2) ? 0 : (NSTAGE - 3) * LPT + LOADS_BEFORE_BARRIER;
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
@@ -320,14 +336,14 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // ---- pipeline prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed ------------------------------
     const int nk = p.nk;
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s) {
+    for (int s = 0; s < PRE; ++s) {
         if (s < nk) {
 #pragma unroll
             for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
             next_tile();
         }
     }
-    if (nk >= NSTAGE - 1) tile_barrier<(NSTAGE - 2) * LPT>();
+    if (nk >= PRE) tile_barrier<(PRE - 1) * LPT>();
     else tile_barrier<0>();
 
     Frag fa[2][TM], fb[2][TN];
@@ -344,11 +360,11 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // steady state, the drain and the last tile so that the hot loop carries no branches.
     int stage = 0;
     auto k_tile = [&](auto more_c, auto has_next_c, auto parity_c) {
-        constexpr bool more = decltype(more_c)::value;          // tile kt+NSTAGE-1 exists: load it
+        constexpr bool more = decltype(more_c)::value;          // tile kt+PRE exists: load it
         constexpr bool has_next = decltype(has_next_c)::value;  // tile kt+1 exists
         constexpr int parity = decltype(parity_c)::value;       // fragment buffer holding this tile's k-step 0
         const unsigned stage_base = lds0 + stage * STAGE_BYTES;
-        int pre = stage + NSTAGE - 1;
+        int pre = TWO_STAGE ? stage : stage + NSTAGE - 1;   // stage the loads of this iteration go to
         if (pre >= NSTAGE) pre -= NSTAGE;
         int next = stage + 1;
         if (next == NSTAGE) next = 0;
@@ -361,7 +377,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 // fragments of this tile are all in registers (or being read from an older barrier's
                 // tile); tile kt+1 must be visible, and nobody may still read the stage that the
                 // next iteration's loads overwrite
-                if (more) tile_barrier<(NSTAGE - 3) * LPT + LOADS_BEFORE_BARRIER>();
+                if (more) tile_barrier<STEADY_VMCNT>();
                 else tile_barrier<0>();
             }
             const unsigned rbase = last ? next_base : stage_base;
@@ -390,11 +406,19 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-                if (more) {
+                if (more && !TWO_STAGE) {
                     const int f = ks * NM + m;
 #pragma unroll
                     for (int idx = 0; idx < LPT; ++idx) {
                         if (idx < (f * LPT) / TOT || idx >= ((f + 1) * LPT) / TOT) continue;
+                        issue_load(idx, pre);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if (more && TWO_STAGE && last) {
+#pragma unroll
+                    for (int idx = 0; idx < LPT; ++idx) {
+                        if (idx < (m * LPT) / NM || idx >= ((m + 1) * LPT) / NM) continue;
                         issue_load(idx, pre);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -426,7 +450,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             k_tile(F{}, T{}, P0{});
             k_tile(F{}, F{}, P1{});
         } else {
-            for (; kt + NSTAGE - 1 < nk; ++kt) k_tile(T{}, T{}, P0{});
+            for (; kt + PRE < nk; ++kt) k_tile(T{}, T{}, P0{});
             for (; kt + 1 < nk; ++kt) k_tile(F{}, T{}, P0{});
             k_tile(F{}, F{}, P0{});
         }
