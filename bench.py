@@ -281,15 +281,26 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
                         "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
         Qv = buf[: n * Mb * Kb].view(n, Mb, Kb)
         Rv = buf[: n * Kb * Nb].view(n, Kb, Nb)
-        for k, fn in (("bwd_dx", lambda: c3.cube3d_linear_bwd_dx(d, c3.ALL_RANKS, gb, wb, Qv, wsb[c3.OP_BWD_DX])),
-                      ("bwd_dw", lambda: c3.cube3d_linear_bwd_dw(d, c3.ALL_RANKS, xb, gb, Rv, wsb[c3.OP_BWD_DW]))):
+        dxsh = torch.empty((n, Ms, Kb), dtype=i16, device="cuda")
+        dwsh = torch.empty((n, Kb, Ns), dtype=i16, device="cuda")
+        for k, fn, nbytes in (
+                ("bwd_dx", lambda: c3.cube3d_linear_bwd_dx(d, c3.ALL_RANKS, gb, wb, Qv, wsb[c3.OP_BWD_DX]), None),
+                ("reduce_scatter_dx", lambda: c3.virtual_cube_reduce_scatter(d, c3.OPERAND_DX, in_axis, Qv, dxsh),
+                 Qv.numel() * 4 + dxsh.numel() * 2),
+                ("bwd_dw", lambda: c3.cube3d_linear_bwd_dw(d, c3.ALL_RANKS, xb, gb, Rv, wsb[c3.OP_BWD_DW]), None),
+                ("reduce_scatter_dw", lambda: c3.virtual_cube_reduce_scatter(d, c3.OPERAND_DW, c3.AXIS_X, Rv, dwsh),
+                 Rv.numel() * 4 + dwsh.numel() * 2)):
             fn()
             ms = timed(fn, 10)
-            r[k] = {"avg_us": round(ms * 1e3, 1), "tflops": round(flop / (ms * 1e-3) / 1e12, 1)}
-            tot_flop += flop
-            tot_ms += ms
+            if nbytes is None:
+                r[k] = {"avg_us": round(ms * 1e3, 1), "tflops": round(flop / (ms * 1e-3) / 1e12, 1)}
+                tot_flop += flop
+                tot_ms += ms
+            else:
+                r[k] = {"avg_us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                        "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
         res[name] = r
-        del xs, ws, gs, xb, wb, gb, P, ysh, Qv, Rv, buf
+        del xs, ws, gs, xb, wb, gb, P, ysh, Qv, Rv, buf, dxsh, dwsh
         torch.cuda.empty_cache()
     res["products_tflops"] = round(tot_flop / (tot_ms * 1e-3) / 1e12, 1)
     res["frac_of_bf16_peak"] = round(res["products_tflops"] / PEAK_TFLOPS["bf16"], 4)

@@ -100,28 +100,53 @@ __device__ __forceinline__ RowMap map_copy_row(const CubeGeom &g, int mode, int 
     return m;
 }
 
-// VEC = bytes moved per lane per step; es = element size in bytes.
+// VecT = what one lane moves per step; es = element size in bytes.  A wavefront works on the
+// four rows it owns in its block at the same time, four pieces per row in flight, so that every
+// lane has up to sixteen independent loads outstanding before the first store (the rows are
+// short: one row alone leaves the memory system idle).
 template <typename VecT>
 __global__ __launch_bounds__(256) void cube_copy_kernel(CubeGeom g, int mode, int64_t rows, int nseg, int es,
                                                         const char *__restrict__ src, char *__restrict__ dst)
 {
+    constexpr int RPW = ROWS_PER_BLOCK / 4;   // rows per wavefront
+    constexpr int U = 4;                      // pieces per row per step
     const int r = blockIdx.z;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK;
-    for (int w = wave; w < ROWS_PER_BLOCK; w += 4) {
-        const int64_t row = row0 + w;
-        if (row >= rows) break;
-        const RowMap m = map_copy_row(g, mode, r, row);
-        const int64_t seg_vecs = m.seg * es / (int64_t)sizeof(VecT);
-        const VecT *s = reinterpret_cast<const VecT *>(src + m.src * es);
-        VecT *d = reinterpret_cast<VecT *>(dst + m.dst * es);
-        const int64_t stride_vecs = m.seg_stride * es / (int64_t)sizeof(VecT);
-        const int64_t total = seg_vecs * nseg;
-        for (int64_t c = lane; c < total; c += 64) {
-            const int64_t p = c / seg_vecs;
-            d[c] = s[p * stride_vecs + (c - p * seg_vecs)];
-        }
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK + wave;
+
+    const VecT *s[RPW];
+    VecT *d[RPW];
+    int64_t seg_vecs = 1, stride_vecs = 0;
+#pragma unroll
+    for (int w = 0; w < RPW; ++w) {
+        const int64_t row = row0 + 4 * w;
+        const RowMap m = map_copy_row(g, mode, r, row < rows ? row : rows - 1);
+        seg_vecs = m.seg * es / (int64_t)sizeof(VecT);
+        stride_vecs = m.seg_stride * es / (int64_t)sizeof(VecT);
+        s[w] = reinterpret_cast<const VecT *>(src + m.src * es);
+        d[w] = reinterpret_cast<VecT *>(dst + m.dst * es);
+    }
+    const int64_t total = seg_vecs * nseg;
+    for (int64_t c0 = lane; c0 < total; c0 += 64 * U) {
+        VecT v[RPW][U];
+#pragma unroll
+        for (int w = 0; w < RPW; ++w)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = c0 + 64 * u;
+                if (c < total && row0 + 4 * w < rows) {
+                    const int64_t p = nseg == 1 ? 0 : c / seg_vecs;
+                    v[w][u] = s[w][p * stride_vecs + (c - p * seg_vecs)];
+                }
+            }
+#pragma unroll
+        for (int w = 0; w < RPW; ++w)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = c0 + 64 * u;
+                if (c < total && row0 + 4 * w < rows) d[w][c] = v[w][u];
+            }
     }
 }
 
@@ -142,17 +167,19 @@ template <typename T, int V> struct __attribute__((aligned(sizeof(T) * V))) Pack
     T v[V];
 };
 
-// Sum over the q partials of a reduce direction, fp32, ascending index, one
-// rounding at the store.  V elements per lane per step.
+// Sum over the q partials of a reduce direction, fp32, ascending index, one rounding at the
+// store.  V elements per lane per step; the loads of up to four partials are in flight together.
 template <typename TIn, typename TOut, int V>
 __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, int64_t rows,
                                                           const TIn *__restrict__ partials, TOut *__restrict__ shards)
 {
+    constexpr int RPW = ROWS_PER_BLOCK / 4;
+    constexpr int QU = 4;                     // partials loaded together
     const int r = blockIdx.z;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const Coords c = decode_rank(g, r);
-    const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK;
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK + wave;
 
     int64_t seg, src0, src_step, src_ld, dst_ld, src_row0, src_col0;
     if (mode == MV_REDUCE_Y) {  // keep row panel b of the sum over b'
@@ -169,23 +196,28 @@ __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, 
         src_step = (rank_index(g, 1 % g.q, c.a, c.b) - rank_index(g, 0, c.a, c.b)) * g.Kb * g.Nb;
     }
     const int64_t dst_rows = mode == MV_REDUCE_DW ? g.Kb : g.Ms;
+    const int q = g.q;
 
-    for (int w = wave; w < ROWS_PER_BLOCK; w += 4) {
-        const int64_t row = row0 + w;
+    for (int w = 0; w < RPW; ++w) {
+        const int64_t row = row0 + 4 * w;
         if (row >= rows) break;
         const TIn *s = partials + src0 + (src_row0 + row) * src_ld + src_col0;
         TOut *d = shards + ((int64_t)r * dst_rows + row) * dst_ld;
         for (int64_t e = (int64_t)lane * V; e < seg; e += 64 * V) {
             float acc[V];
-            {
-                const Pack<TIn, V> p = *reinterpret_cast<const Pack<TIn, V> *>(s + e);
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] = load_f32<TIn>(&p.v[v]);
-            }
-            for (int k = 1; k < g.q; ++k) {
-                const Pack<TIn, V> p = *reinterpret_cast<const Pack<TIn, V> *>(s + k * src_step + e);
+            for (int v = 0; v < V; ++v) acc[v] = 0.f;
+            for (int k0 = 0; k0 < q; k0 += QU) {
+                Pack<TIn, V> p[QU];
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] += load_f32<TIn>(&p.v[v]);
+                for (int u = 0; u < QU; ++u)
+                    if (k0 + u < q) p[u] = *reinterpret_cast<const Pack<TIn, V> *>(s + (k0 + u) * src_step + e);
+#pragma unroll
+                for (int u = 0; u < QU; ++u)          // ascending index along the reduce direction
+                    if (k0 + u < q) {
+#pragma unroll
+                        for (int v = 0; v < V; ++v) acc[v] += load_f32<TIn>(&p[u].v[v]);
+                    }
             }
             Pack<TOut, V> o;
 #pragma unroll
