@@ -207,6 +207,80 @@ class Cube:
             out[i, j, l] = acc
         return out
 
+    # ---- vector parameters (Section 3.1.1, the paragraph on vectors; Algorithms 7 and 8) -----
+    # A vector b of length N lives on the diagonal of the weight plane: only processors whose
+    # y and z indices coincide hold a piece, b[j*Nb + i*Ns : +Ns] on processor (i, j, j).  For the
+    # output-side add Y + b the pieces are broadcast along the output direction and all-gathered
+    # along x, so that every processor has the Nb entries of its output block.  The printed
+    # backward (Algorithm 8) only reduce-scatters along x on the diagonal; the broadcast's own
+    # adjoint, a reduce along the broadcast direction onto the diagonal, is needed before it or
+    # the rows held off the diagonal would be lost.  Both are taken here.
+    def holds_bias(self, i, j, l):
+        return j == l
+
+    def bias_shard_slice(self, i, j, l):
+        """Slice of b held by the diagonal processor (i, j, l = j)."""
+        if j != l:
+            raise ValueError("only diagonal processors hold vector parameters")
+        s0 = j * self.Nb + i * self.Ns
+        return slice(s0, s0 + self.Ns)
+
+    def shard_bias(self, b, fill=0.0):
+        """Vector of length N -> cube array [q,q,q,Ns]; processors off the diagonal get `fill`."""
+        b = np.asarray(b)
+        if b.shape != (self.N,):
+            raise ValueError("bias has shape %r, expected (%d,)" % (b.shape, self.N))
+        q = self.q
+        out = np.full((q, q, q, self.Ns), fill, dtype=b.dtype)
+        for i, j, l in self.ranks():
+            if j == l:
+                out[i, j, l] = b[self.bias_shard_slice(i, j, l)]
+        return out
+
+    def unshard_bias(self, shards):
+        shards = np.asarray(shards)
+        b = np.zeros((self.N,), dtype=shards.dtype)
+        count = np.zeros((self.N,), dtype=np.int32)
+        for i, j, l in self.ranks():
+            if j == l:
+                s = self.bias_shard_slice(i, j, l)
+                b[s] = shards[i, j, l]
+                count[s] += 1
+        if not np.all(count == 1):
+            raise AssertionError("bias pieces do not tile the vector exactly once")
+        return b
+
+    def gather_bias(self, shards):
+        """Algorithm 7 steps 1-2 for the output-side add: every processor gets the Nb entries
+        of its output block (block index = its index a along the input direction)."""
+        q = self.q
+        out = np.empty((q, q, q, self.Nb), dtype=np.asarray(shards).dtype)
+        for i, j, l in self.ranks():
+            a, _ = self.ab(i, j, l)
+            out[i, j, l] = np.concatenate([shards[i2, a, a] for i2 in range(q)])
+        return out
+
+    def add_bias(self, y_shards, bias_blocks):
+        """Algorithm 7 step 3 on the output shards [Ms, Nb]: every row gets the block's bias."""
+        return np.asarray(y_shards, dtype=np.float64) + np.asarray(bias_blocks, dtype=np.float64)[:, :, :, None, :]
+
+    def bias_backward(self, dy_shards):
+        """Algorithm 8: column sums of every processor's dY shard, reduced along the output
+        direction onto the diagonal and reduce-scattered along x; zeros off the diagonal."""
+        q, Ns = self.q, self.Ns
+        out = np.zeros((q, q, q, Ns), dtype=np.float64)
+        for i, j, l in self.ranks():
+            if j != l:
+                continue
+            blk = j                         # the diagonal index is the output-block index
+            acc = np.zeros((Ns,), dtype=np.float64)
+            for i2 in range(q):
+                for b2 in range(q):
+                    sh = np.asarray(dy_shards[self.rank_of(i2, blk, b2)], dtype=np.float64)
+                    acc += sh[:, i * Ns:(i + 1) * Ns].sum(axis=0)
+            out[i, j, l] = acc
+        return out
+
     # ---- cost formulas (Section 3.1.1 memory, Section 3.1.2 compute/comm) ---
     def memory_per_rank(self):
         return self.Ms * self.Kb + self.Kb * self.Ns + self.Ms * self.Nb

@@ -124,6 +124,20 @@ def test_workspace_query_and_strings(lib):
     assert e.value.status == c3.ESHAPE
 
 
+def test_workspace_too_small_is_reported_before_any_launch(lib):
+    # one 128x128 output tile with a long contraction: the plan splits K and needs fp32 partials
+    d = c3.make_desc(1, 128, 8192, 128, in_dtype=c3.BF16, out_dtype=c3.BF16)
+    need = c3.cube3d_workspace_bytes(d, c3.OP_FWD, False)
+    assert need > 0 and need % (128 * 128 * 4) == 0
+    assert fwd(lib, d, ws=None, ws_bytes=0) == c3.EWORKSPACE
+    assert fwd(lib, d, ws=FAKE, ws_bytes=need - 1) == c3.EWORKSPACE
+    assert fwd(lib, d, ws=ODD, ws_bytes=need) == c3.EINVAL
+    # the same layer on a cube with many processors has enough tiles: no workspace
+    big = c3.make_desc(4, 32768, 8192, 32768, in_dtype=c3.BF16, out_dtype=c3.BF16)
+    for op in (c3.OP_FWD, c3.OP_BWD_DX, c3.OP_BWD_DW):
+        assert c3.cube3d_workspace_bytes(big, op, False) == 0
+
+
 def test_binding_refuses_host_tensors():
     import torch
     d = good()
