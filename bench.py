@@ -299,8 +299,21 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
             else:
                 r[k] = {"avg_us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                         "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
+        # bias (Algorithms 7-8): block gather, reduce-scatter with the add fused, gradient from the dY shards
+        b_diag = torch.randn((n, Ns), device="cuda", generator=g)
+        b_blk = torch.empty((n, Nb), dtype=f32, device="cuda")
+        db = torch.empty((n, Ns), dtype=f32, device="cuda")
+        for k, fn, nbytes in (
+                ("bias_gather", lambda: c3.virtual_cube_bias_gather(d, b_diag, b_blk), (q * q * Ns + n * Nb) * 4),
+                ("reduce_scatter_y_bias", lambda: c3.virtual_cube_reduce_scatter_bias(d, out_axis, P, b_blk, ysh),
+                 P.numel() * 4 + ysh.numel() * 2 + b_blk.numel() * 4),
+                ("bias_bwd", lambda: c3.virtual_cube_bias_bwd(d, gs, db), gs.numel() * 2 + q * q * Ns * 4)):
+            fn()
+            ms = timed(fn, 10)
+            r[k] = {"avg_us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
         res[name] = r
-        del xs, ws, gs, xb, wb, gb, P, ysh, Qv, Rv, buf, dxsh, dwsh
+        del xs, ws, gs, xb, wb, gb, P, ysh, Qv, Rv, buf, dxsh, dwsh, b_diag, b_blk, db
         torch.cuda.empty_cache()
     res["products_tflops"] = round(tot_flop / (tot_ms * 1e-3) / 1e12, 1)
     res["frac_of_bf16_peak"] = round(res["products_tflops"] / PEAK_TFLOPS["bf16"], 4)

@@ -92,7 +92,8 @@ typedef enum cube3d_operand {
     CUBE3D_OPERAND_DY = 2,
     CUBE3D_OPERAND_Y = 3,
     CUBE3D_OPERAND_DX = 4,
-    CUBE3D_OPERAND_DW = 5
+    CUBE3D_OPERAND_DW = 5,
+    CUBE3D_OPERAND_BIAS = 6 /* vector parameter of length N (scatter / assemble only) */
 } cube3d_operand;
 
 typedef enum cube3d_op {
@@ -195,12 +196,40 @@ int virtual_cube_reduce_scatter(const cube3d_desc *desc, int which, int axis,
  *   which = X / DX : full [M, K] <-> cube buffer of [Ms, Kb]
  *   which = W / DW : full [K, N] <-> cube buffer of [Kb, Ns]
  *   which = Y / DY : full [M, N] <-> cube buffer of [Ms, Nb]
+ *   which = BIAS   : full [N] fp32 <-> diagonal storage (see the vector-parameter calls below)
  * X, W, DY are in_dtype; Y, DX, DW are shard_dtype.  Bit-for-bit copies.
  */
 int virtual_cube_scatter(const cube3d_desc *desc, int which,
                          const void *full, void *shards, void *stream);
 int virtual_cube_assemble(const cube3d_desc *desc, int which,
                           const void *shards, void *full, void *stream);
+
+/*
+ * Vector parameters: the bias b of Y = X W + b (Section 3.1.1, paragraph on vectors;
+ * Algorithms 7 and 8).  b has length N and is fp32 here, and so is its gradient.
+ *
+ * Diagonal storage: a cube buffer of [Ns] fp32 per processor in which only the processors
+ * whose y and z indices coincide hold data, processor (i, j, j) holding b[j*Nb + i*Ns : +Ns].
+ * Entries of the other processors are ignored on input and written as zero on output.
+ * virtual_cube_scatter / virtual_cube_assemble with which = CUBE3D_OPERAND_BIAS convert
+ * between the full vector [N] and this storage.
+ *
+ * virtual_cube_bias_gather: Algorithm 7 steps 1-2 for the output-side add: broadcast along the
+ *   output direction, all-gather along x.  bias_blocks: cube buffer of [Nb] fp32; every
+ *   processor receives the Nb entries of its output block.
+ * virtual_cube_reduce_scatter_bias: Algorithm 1 step 4 followed by Algorithm 7 step 3 in one
+ *   pass: Y shard = (sum of the q partials along `axis`, fp32, ascending) + bias block, rounded
+ *   once to shard_dtype.  `axis` must be the output direction.
+ * virtual_cube_bias_bwd: Algorithm 8: db = column sums of dY.  dY_shards: cube buffer of
+ *   [Ms, Nb] in_dtype (fp8 codes are multiplied by scale_dy); dbias_diag: diagonal storage.
+ *   The sums run over the rows in a fixed order in fp32 (run-to-run identical).  The printed
+ *   algorithm reduces along x only; the reduce along the output direction onto the diagonal
+ *   (the adjoint of Algorithm 7's broadcast) is included, otherwise rows would be lost.
+ */
+int virtual_cube_bias_gather(const cube3d_desc *desc, const void *bias_diag, void *bias_blocks, void *stream);
+int virtual_cube_reduce_scatter_bias(const cube3d_desc *desc, int axis, const void *partials, const void *bias_blocks,
+                                     void *shards, void *stream);
+int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *stream);
 
 const char *cube3d_status_string(int status);
 int cube3d_version(void);

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libcube3d.so")
 OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH, ENOTIMPL = 0, -1, -2, -3, -4, -5, -6
 F32, BF16, FP8_E4M3 = 0, 1, 2
 AXIS_X, AXIS_Y, AXIS_Z = 0, 1, 2
-OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW = range(6)
+OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW, OPERAND_BIAS = range(7)
 OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
 ALL_RANKS = (-1, -1, -1)
 
@@ -76,6 +76,12 @@ def load():
         f = getattr(lib, name)
         f.argtypes = [dp, ci, vp, vp, vp]
         f.restype = ci
+    lib.virtual_cube_bias_gather.argtypes = [dp, vp, vp, vp]
+    lib.virtual_cube_bias_gather.restype = ci
+    lib.virtual_cube_reduce_scatter_bias.argtypes = [dp, ci, vp, vp, vp, vp]
+    lib.virtual_cube_reduce_scatter_bias.restype = ci
+    lib.virtual_cube_bias_bwd.argtypes = [dp, vp, vp, vp]
+    lib.virtual_cube_bias_bwd.restype = ci
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
     lib.cube3d_version.restype = ci
@@ -85,7 +91,8 @@ def load():
 
 EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", "cube3d_workspace_bytes",
            "virtual_cube_gather", "virtual_cube_reduce_scatter", "virtual_cube_scatter",
-           "virtual_cube_assemble", "cube3d_status_string", "cube3d_version")
+           "virtual_cube_assemble", "virtual_cube_bias_gather", "virtual_cube_reduce_scatter_bias",
+           "virtual_cube_bias_bwd", "cube3d_status_string", "cube3d_version")
 
 
 def status_string(status: int) -> str:
@@ -164,3 +171,21 @@ def virtual_cube_assemble(desc, which, shards, full, stream=None):
     _check(load().virtual_cube_assemble(ctypes.byref(desc), which, _ptr(shards), _ptr(full), _stream(stream)),
            "virtual_cube_assemble")
     return full
+
+
+def virtual_cube_bias_gather(desc, bias_diag, bias_blocks, stream=None):
+    _check(load().virtual_cube_bias_gather(ctypes.byref(desc), _ptr(bias_diag), _ptr(bias_blocks), _stream(stream)),
+           "virtual_cube_bias_gather")
+    return bias_blocks
+
+
+def virtual_cube_reduce_scatter_bias(desc, axis, partials, bias_blocks, shards, stream=None):
+    _check(load().virtual_cube_reduce_scatter_bias(ctypes.byref(desc), axis, _ptr(partials), _ptr(bias_blocks),
+                                                   _ptr(shards), _stream(stream)), "virtual_cube_reduce_scatter_bias")
+    return shards
+
+
+def virtual_cube_bias_bwd(desc, dY_shards, dbias_diag, stream=None):
+    _check(load().virtual_cube_bias_bwd(ctypes.byref(desc), _ptr(dY_shards), _ptr(dbias_diag), _stream(stream)),
+           "virtual_cube_bias_bwd")
+    return dbias_diag

@@ -184,7 +184,42 @@ int virtual_cube_reduce_scatter(const cube3d_desc *desc, int which, int axis, co
     case CUBE3D_OPERAND_DW: if (axis != CUBE3D_AXIS_X) return CUBE3D_EINVAL; mode = MV_REDUCE_DW; break;
     default: return CUBE3D_EINVAL;
     }
-    return cube_reduce(g, mode, desc->out_dtype, desc->shard_dtype, partials, shards, static_cast<hipStream_t>(stream));
+    return cube_reduce(g, mode, desc->out_dtype, desc->shard_dtype, partials, shards, nullptr,
+                       static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_reduce_scatter_bias(const cube3d_desc *desc, int axis, const void *partials, const void *bias_blocks,
+                                     void *shards, void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(desc, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!partials || !shards || !bias_blocks || misaligned(partials) || misaligned(shards) || misaligned(bias_blocks))
+        return CUBE3D_EINVAL;
+    const int out_axis = desc->in_axis == CUBE3D_AXIS_Y ? CUBE3D_AXIS_Z : CUBE3D_AXIS_Y;
+    if (axis != out_axis) return CUBE3D_EINVAL;
+    return cube_reduce(g, MV_REDUCE_Y, desc->out_dtype, desc->shard_dtype, partials, shards,
+                       static_cast<const float *>(bias_blocks), static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_bias_gather(const cube3d_desc *desc, const void *bias_diag, void *bias_blocks, void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(desc, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!bias_diag || !bias_blocks || misaligned(bias_diag) || misaligned(bias_blocks)) return CUBE3D_EINVAL;
+    return cube_bias_move(g, MV_GATHER_BIAS, static_cast<const float *>(bias_diag), static_cast<float *>(bias_blocks),
+                          static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(desc, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!dY_shards || !dbias_diag || misaligned(dY_shards) || misaligned(dbias_diag)) return CUBE3D_EINVAL;
+    return cube_bias_bwd(g, desc->in_dtype, desc->scale_dy, dY_shards, static_cast<float *>(dbias_diag),
+                         static_cast<hipStream_t>(stream));
 }
 
 static int storage_move(const cube3d_desc *desc, int which, bool scatter, const void *src, void *dst, void *stream)
@@ -193,6 +228,9 @@ static int storage_move(const cube3d_desc *desc, int which, bool scatter, const 
     int rc = check_desc(desc, &g);
     if (rc != CUBE3D_OK) return rc;
     if (!src || !dst || misaligned(src) || misaligned(dst)) return CUBE3D_EINVAL;
+    if (which == CUBE3D_OPERAND_BIAS)
+        return cube_bias_move(g, scatter ? MV_SCATTER_BIAS : MV_ASSEMBLE_BIAS, static_cast<const float *>(src),
+                              static_cast<float *>(dst), static_cast<hipStream_t>(stream));
     int mode, es;
     switch (which) {
     case CUBE3D_OPERAND_X: mode = scatter ? MV_SCATTER_X : MV_ASSEMBLE_X; es = elem_size(desc->in_dtype); break;

@@ -171,7 +171,8 @@ template <typename T, int V> struct __attribute__((aligned(sizeof(T) * V))) Pack
 // store.  V elements per lane per step; the loads of up to four partials are in flight together.
 template <typename TIn, typename TOut, int V>
 __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, int64_t rows,
-                                                          const TIn *__restrict__ partials, TOut *__restrict__ shards)
+                                                          const TIn *__restrict__ partials, TOut *__restrict__ shards,
+                                                          const float *__restrict__ bias)
 {
     constexpr int RPW = ROWS_PER_BLOCK / 4;
     constexpr int QU = 4;                     // partials loaded together
@@ -219,6 +220,11 @@ __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, 
                         for (int v = 0; v < V; ++v) acc[v] += load_f32<TIn>(&p[u].v[v]);
                     }
             }
+            if (bias) {   // Algorithm 7 step 3: the output block's bias, added to the finished sum
+                const Pack<float, V> b = *reinterpret_cast<const Pack<float, V> *>(bias + (int64_t)r * g.Nb + e);
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] += b.v[v];
+            }
             Pack<TOut, V> o;
 #pragma unroll
             for (int v = 0; v < V; ++v) store_f32<TOut>(&o.v[v], acc[v]);
@@ -229,15 +235,15 @@ __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, 
 
 template <typename TIn, typename TOut>
 int launch_reduce(const CubeGeom &g, int mode, int64_t rows, int64_t seg, const void *partials, void *shards,
-                  hipStream_t stream)
+                  const float *bias, hipStream_t stream)
 {
     dim3 grid((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), 1, (unsigned)(g.q * g.q * g.q));
     const TIn *p = static_cast<const TIn *>(partials);
     TOut *s = static_cast<TOut *>(shards);
     if (seg % 4 == 0)
-        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 4>), grid, dim3(256), 0, stream, g, mode, rows, p, s);
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 4>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
     else
-        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 1>), grid, dim3(256), 0, stream, g, mode, rows, p, s);
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 1>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
     return launch_status();
 }
 
@@ -277,8 +283,9 @@ int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, h
 }
 
 int cube_reduce(const CubeGeom &g, int mode, int partial_dtype, int shard_dtype, const void *partials, void *shards,
-                hipStream_t stream)
+                const float *bias, hipStream_t stream)
 {
+    if (bias && mode != MV_REDUCE_Y) return CUBE3D_EINVAL;
     int64_t rows, seg;
     switch (mode) {
     case MV_REDUCE_Y: rows = g.Ms; seg = g.Nb; break;
@@ -288,14 +295,132 @@ int cube_reduce(const CubeGeom &g, int mode, int partial_dtype, int shard_dtype,
     }
     if (g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;
     if (partial_dtype == CUBE3D_F32 && shard_dtype == CUBE3D_F32)
-        return launch_reduce<float, float>(g, mode, rows, seg, partials, shards, stream);
+        return launch_reduce<float, float>(g, mode, rows, seg, partials, shards, bias, stream);
     if (partial_dtype == CUBE3D_F32 && shard_dtype == CUBE3D_BF16)
-        return launch_reduce<float, unsigned short>(g, mode, rows, seg, partials, shards, stream);
+        return launch_reduce<float, unsigned short>(g, mode, rows, seg, partials, shards, bias, stream);
     if (partial_dtype == CUBE3D_BF16 && shard_dtype == CUBE3D_F32)
-        return launch_reduce<unsigned short, float>(g, mode, rows, seg, partials, shards, stream);
+        return launch_reduce<unsigned short, float>(g, mode, rows, seg, partials, shards, bias, stream);
     if (partial_dtype == CUBE3D_BF16 && shard_dtype == CUBE3D_BF16)
-        return launch_reduce<unsigned short, unsigned short>(g, mode, rows, seg, partials, shards, stream);
+        return launch_reduce<unsigned short, unsigned short>(g, mode, rows, seg, partials, shards, bias, stream);
     return CUBE3D_EDTYPE;
+}
+
+// ---- vector parameters (Section 3.1.1; Algorithms 7 and 8) ---------------------------------------------
+namespace {
+
+// One block per destination processor (scatter, gather) or per source processor (assemble).
+__global__ __launch_bounds__(256) void cube_bias_move_kernel(CubeGeom g, int mode, const float *__restrict__ src,
+                                                             float *__restrict__ dst)
+{
+    const int r = blockIdx.x;
+    const int l = r % g.q, j = (r / g.q) % g.q, i = r / (g.q * g.q);
+    if (mode == MV_SCATTER_BIAS) {
+        for (int64_t e = threadIdx.x; e < g.Ns; e += 256)
+            dst[(int64_t)r * g.Ns + e] = (j == l) ? src[(int64_t)j * g.Nb + (int64_t)i * g.Ns + e] : 0.f;
+    } else if (mode == MV_ASSEMBLE_BIAS) {
+        if (j != l) return;
+        for (int64_t e = threadIdx.x; e < g.Ns; e += 256)
+            dst[(int64_t)j * g.Nb + (int64_t)i * g.Ns + e] = src[(int64_t)r * g.Ns + e];
+    } else {  // MV_GATHER_BIAS: piece i' of block a comes from the diagonal processor (i', a, a)
+        const int a = g.in_axis_z ? l : j;
+        for (int64_t c = threadIdx.x; c < g.Nb; c += 256) {
+            const int64_t i2 = c / g.Ns, e = c - i2 * g.Ns;
+            dst[(int64_t)r * g.Nb + c] = src[((i2 * g.q + a) * g.q + a) * g.Ns + e];
+        }
+    }
+}
+
+template <typename T> __device__ __forceinline__ float dy_value(T raw);
+template <> __device__ __forceinline__ float dy_value<float>(float raw) { return raw; }
+template <> __device__ __forceinline__ float dy_value<unsigned short>(unsigned short raw) { return bf16_bits_to_f32(raw); }
+// fp8 e4m3 "fn": 1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent 0 is subnormal
+template <> __device__ __forceinline__ float dy_value<unsigned char>(unsigned char raw)
+{
+    const int e = (raw >> 3) & 15, m = raw & 7;
+    const float mag = e == 0 ? (float)m * 0.001953125f                                      // m/8 * 2^-6
+                             : __uint_as_float((unsigned)(e + 120) << 23 | (unsigned)m << 20);  // (1+m/8) * 2^(e-7)
+    return (raw & 0x80) ? -mag : mag;
+}
+
+// One block per (diagonal processor (i, a, a), chunk of 64 of its Ns columns).  Lane = column;
+// the four wavefronts take the rows t = 4u + wave of the fixed sequence t = (i'*q + b')*Ms + row
+// over every processor (i', a, b') of the output block's column of the cube; each adds its rows
+// in ascending order, then the four sums are added in wavefront order.  Eight loads in flight.
+template <typename T>
+__global__ __launch_bounds__(256) void cube_bias_bwd_kernel(CubeGeom g, float scale, const T *__restrict__ dy,
+                                                            float *__restrict__ db)
+{
+    __shared__ float part[4][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int i = blockIdx.x / g.q, a = blockIdx.x % g.q;
+    const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+    const bool live = c < g.Ns;
+    const int64_t total = (int64_t)g.q * g.q * g.Ms;
+    float acc = 0.f;
+    constexpr int U = 8;
+    for (int64_t t0 = wave; t0 < total; t0 += 4 * U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t t = t0 + 4 * u;
+            v[u] = 0.f;
+            if (live && t < total) {
+                const int64_t src_rank = t / g.Ms, row = t - src_rank * g.Ms;
+                const int i2 = (int)(src_rank / g.q), b2 = (int)(src_rank % g.q);
+                const int64_t rr = rank_index(g, i2, a, b2);
+                v[u] = dy_value<T>(dy[(rr * g.Ms + row) * g.Nb + (int64_t)i * g.Ns + c]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc += v[u];
+    }
+    part[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && live) {
+        const float s = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        db[(((int64_t)i * g.q + a) * g.q + a) * g.Ns + c] = s * scale;
+    }
+}
+
+__global__ __launch_bounds__(256) void cube_bias_zero_offdiag_kernel(CubeGeom g, float *__restrict__ db)
+{
+    const int r = blockIdx.x;
+    const int l = r % g.q, j = (r / g.q) % g.q;
+    if (j == l) return;
+    for (int64_t e = threadIdx.x; e < g.Ns; e += 256) db[(int64_t)r * g.Ns + e] = 0.f;
+}
+
+}  // namespace
+
+int cube_bias_move(const CubeGeom &g, int mode, const float *src, float *dst, hipStream_t stream)
+{
+    if (mode != MV_SCATTER_BIAS && mode != MV_ASSEMBLE_BIAS && mode != MV_GATHER_BIAS) return CUBE3D_EINVAL;
+    hipLaunchKernelGGL(cube_bias_move_kernel, dim3((unsigned)(g.q * g.q * g.q)), dim3(256), 0, stream, g, mode, src, dst);
+    return launch_status();
+}
+
+int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *dy_shards, float *dbias_diag,
+                  hipStream_t stream)
+{
+    dim3 grid((unsigned)(g.q * g.q), (unsigned)((g.Ns + 63) / 64), 1);
+    if (grid.y > 65535) return CUBE3D_ESHAPE;
+    hipLaunchKernelGGL(cube_bias_zero_offdiag_kernel, dim3((unsigned)(g.q * g.q * g.q)), dim3(256), 0, stream, g, dbias_diag);
+    switch (dy_dtype) {
+    case CUBE3D_F32:
+        hipLaunchKernelGGL((cube_bias_bwd_kernel<float>), grid, dim3(256), 0, stream, g, 1.f,
+                           static_cast<const float *>(dy_shards), dbias_diag);
+        break;
+    case CUBE3D_BF16:
+        hipLaunchKernelGGL((cube_bias_bwd_kernel<unsigned short>), grid, dim3(256), 0, stream, g, 1.f,
+                           static_cast<const unsigned short *>(dy_shards), dbias_diag);
+        break;
+    case CUBE3D_FP8_E4M3:
+        hipLaunchKernelGGL((cube_bias_bwd_kernel<unsigned char>), grid, dim3(256), 0, stream, g, scale_dy,
+                           static_cast<const unsigned char *>(dy_shards), dbias_diag);
+        break;
+    default: return CUBE3D_EDTYPE;
+    }
+    return launch_status();
 }
 
 }  // namespace cube3d

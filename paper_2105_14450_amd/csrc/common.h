@@ -64,12 +64,19 @@ enum MoveMode {
     MV_ASSEMBLE_Y,
     MV_REDUCE_Y,
     MV_REDUCE_DX,
-    MV_REDUCE_DW
+    MV_REDUCE_DW,
+    MV_SCATTER_BIAS,   // full vector -> diagonal storage
+    MV_ASSEMBLE_BIAS,  // diagonal storage -> full vector
+    MV_GATHER_BIAS     // diagonal storage -> one [Nb] block per processor
 };
 
 int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, hipStream_t stream);
+// bias: optional [q^3][Nb] fp32 blocks added to the sum (MV_REDUCE_Y only), or nullptr
 int cube_reduce(const CubeGeom &g, int mode, int partial_dtype, int shard_dtype, const void *partials, void *shards,
-                hipStream_t stream);
+                const float *bias, hipStream_t stream);
+int cube_bias_move(const CubeGeom &g, int mode, const float *src, float *dst, hipStream_t stream);
+int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *dy_shards, float *dbias_diag,
+                  hipStream_t stream);
 
 inline int launch_status()
 {

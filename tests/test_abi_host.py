@@ -110,6 +110,25 @@ def test_collective_argument_errors(lib):
         assert f(ctypes.byref(good(N=6)), c3.OPERAND_X, FAKE, FAKE, None) == c3.ESHAPE
 
 
+def test_bias_argument_errors(lib):
+    d = good()                       # output direction is Z
+    g, r, b = lib.virtual_cube_bias_gather, lib.virtual_cube_reduce_scatter_bias, lib.virtual_cube_bias_bwd
+    assert g(None, FAKE, FAKE, None) == c3.EINVAL
+    assert g(ctypes.byref(d), None, FAKE, None) == c3.EINVAL
+    assert g(ctypes.byref(d), FAKE, ODD, None) == c3.EINVAL
+    assert g(ctypes.byref(good(N=6)), FAKE, FAKE, None) == c3.ESHAPE
+    assert r(ctypes.byref(d), c3.AXIS_Y, FAKE, FAKE, FAKE, None) == c3.EINVAL     # wrong direction
+    assert r(ctypes.byref(d), c3.AXIS_X, FAKE, FAKE, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(d), c3.AXIS_Z, FAKE, None, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(d), c3.AXIS_Z, None, FAKE, FAKE, None) == c3.EINVAL
+    assert r(ctypes.byref(good(in_axis=c3.AXIS_Z)), c3.AXIS_Z, FAKE, FAKE, FAKE, None) == c3.EINVAL
+    assert b(ctypes.byref(d), None, FAKE, None) == c3.EINVAL
+    assert b(ctypes.byref(d), FAKE, ODD, None) == c3.EINVAL
+    assert b(ctypes.byref(good(in_dtype=11)), FAKE, FAKE, None) == c3.EDTYPE
+    for f in (lib.virtual_cube_scatter, lib.virtual_cube_assemble):
+        assert f(ctypes.byref(d), c3.OPERAND_BIAS, None, FAKE, None) == c3.EINVAL
+
+
 def test_workspace_query_and_strings(lib):
     assert c3.cube3d_workspace_bytes(good(M=7), c3.OP_FWD, False) == 0
     assert c3.cube3d_workspace_bytes(good(), 42, False) == 0

@@ -318,3 +318,83 @@ CONFIG3 = [("qkv", 2048, 6144, "y", 31), ("attn_out", 2048, 2048, "z", 32),
 @pytest.mark.parametrize("dist", ["normal", "int"])
 def test_config3_virtual_cube_bf16(name, K, N, ax, seed, dist):
     run_virtual_cube_sampled(4, 8192, K, N, "bf16", dist, seed + (100 if dist == "int" else 0), ax)
+
+
+# ---- bias: Y = X W + b and its gradient (Algorithms 7 and 8) on the virtual cube ---------------------
+TID_BIAS = 4
+
+
+def run_bias(q, M, K, N, dtype, dist, seed, ax):
+    exact = dist == "int"
+    shard_dtype = "f32" if dtype == "f32" else "bf16"
+    inp = synth.linear_inputs(M, K, N, dtype, dist, seed)
+    val = _decode_inputs(inp, dtype)
+    bias = synth.draw((N,), dist, seed, TID_BIAS)                      # fp32 parameter
+    cube = Cube(q, M, K, N, ax)
+    d = _desc(q, M, K, N, dtype, "f32", shard_dtype, ax, inp)
+    out_axis = c3.AXIS_Z if ax == "y" else c3.AXIS_Y
+    n = q ** 3
+    dev = {k: gu.to_device(raw) for k, (raw, _) in inp.items()}
+    # storage of the vector on the diagonal, and the per-processor blocks
+    b_full = gu.to_device(bias)
+    b_diag = gu.empty((n, cube.Ns), "f32")
+    c3.virtual_cube_scatter(d, c3.OPERAND_BIAS, b_full, b_diag)
+    assert np.array_equal(b_diag.cpu().numpy().reshape(q, q, q, cube.Ns), cube.shard_bias(bias))
+    b_blk = gu.empty((n, cube.Nb), "f32")
+    c3.virtual_cube_bias_gather(d, b_diag, b_blk)
+    assert np.array_equal(b_blk.cpu().numpy().reshape(q, q, q, cube.Nb), cube.gather_bias(cube.shard_bias(bias)))
+    back = gu.empty((N,), "f32")
+    c3.virtual_cube_assemble(d, c3.OPERAND_BIAS, b_diag, back)
+    assert np.array_equal(back.cpu().numpy(), bias)
+    # forward with the bias fused into the reduce-scatter
+    xs, ws, gs = gu.empty((n, cube.Ms, cube.Kb), dtype), gu.empty((n, cube.Kb, cube.Ns), dtype), \
+        gu.empty((n, cube.Ms, cube.Nb), dtype)
+    c3.virtual_cube_scatter(d, c3.OPERAND_X, dev["X"], xs)
+    c3.virtual_cube_scatter(d, c3.OPERAND_W, dev["W"], ws)
+    c3.virtual_cube_scatter(d, c3.OPERAND_DY, dev["dY"], gs)
+    xb, wb = gu.empty((n, cube.Mb, cube.Kb), dtype), gu.empty((n, cube.Kb, cube.Nb), dtype)
+    c3.virtual_cube_gather(d, c3.OPERAND_X, AX[ax], xs, xb)
+    c3.virtual_cube_gather(d, c3.OPERAND_W, c3.AXIS_X, ws, wb)
+    P = gu.empty((n, cube.Mb, cube.Nb), "f32")
+    c3.cube3d_linear_fwd(d, c3.ALL_RANKS, xb, wb, P, gu.workspace(d, c3.OP_FWD, True))
+    ys = gu.empty((n, cube.Ms, cube.Nb), shard_dtype)
+    c3.virtual_cube_reduce_scatter_bias(d, out_axis, P, b_blk, ys)
+    Yf = gu.empty((M, N), shard_dtype)
+    c3.virtual_cube_assemble(d, c3.OPERAND_Y, ys, Yf)
+    # gradient of the bias from the dY shards
+    db_diag = gu.empty((n, cube.Ns), "f32")
+    c3.virtual_cube_bias_bwd(d, gs, db_diag)
+    db_full = gu.empty((N,), "f32")
+    c3.virtual_cube_assemble(d, c3.OPERAND_BIAS, db_diag, db_full)
+    torch.cuda.synchronize()
+
+    Yref = om.forward(val["X"], val["W"], 8) + bias.astype(np.float64)[None, :]
+    _check(gu.to_host(Yf, shard_dtype), numfmt.round_to(Yref, shard_dtype) if exact else Yref, dtype, exact,
+           "Y = XW + b", shard_dtype)
+    db_ref = cube.bias_backward(cube.shard_y(val["dY"]))
+    got = db_diag.cpu().numpy().astype(np.float64).reshape(q, q, q, cube.Ns)
+    if exact:
+        assert np.array_equal(got, db_ref)
+        assert np.array_equal(db_full.cpu().numpy().astype(np.float64), val["dY"].sum(axis=0))
+    else:
+        # fp32 running sums over M terms: allow 1e-4 of the largest column sum
+        assert gu.scaled_max_err(got, db_ref) <= 1e-4
+        assert gu.scaled_max_err(db_full.cpu().numpy().astype(np.float64), val["dY"].sum(axis=0)) <= 1e-4
+    # deterministic: a second run gives the same bits
+    db2 = gu.empty((n, cube.Ns), "f32")
+    c3.virtual_cube_bias_bwd(d, gs, db2)
+    torch.cuda.synchronize()
+    assert np.array_equal(db2.cpu().numpy(), db_diag.cpu().numpy())
+
+
+@pytest.mark.parametrize("q,M,K,N,dtype,ax", [(2, 256, 128, 128, "f32", "y"), (2, 256, 128, 128, "f32", "z"),
+                                              (3, 450, 135, 153, "bf16", "y"), (3, 450, 135, 153, "fp8_e4m3", "z"),
+                                              (1, 5, 3, 7, "f32", "y"), (2, 1024, 512, 1024, "bf16", "z")])
+@pytest.mark.parametrize("dist,seed", [("normal", 51), ("int", 151)])
+def test_bias_virtual_cube(q, M, K, N, dtype, ax, dist, seed):
+    run_bias(q, M, K, N, dtype, "uniform" if (dist == "normal" and dtype == "f32") else dist, seed, ax)
+
+
+@pytest.mark.parametrize("dist,seed", [("normal", 52), ("int", 152)])
+def test_bias_config3_qkv_full_size(dist, seed):
+    run_bias(4, 8192, 2048, 6144, "bf16", dist, seed, "y")
