@@ -303,11 +303,12 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
         b_diag = torch.randn((n, Ns), device="cuda", generator=g)
         b_blk = torch.empty((n, Nb), dtype=f32, device="cuda")
         db = torch.empty((n, Ns), dtype=f32, device="cuda")
+        db_ws = torch.empty(c3.cube3d_workspace_bytes(d, c3.OP_BIAS_BWD, True), dtype=torch.uint8, device="cuda")
         for k, fn, nbytes in (
                 ("bias_gather", lambda: c3.virtual_cube_bias_gather(d, b_diag, b_blk), (q * q * Ns + n * Nb) * 4),
                 ("reduce_scatter_y_bias", lambda: c3.virtual_cube_reduce_scatter_bias(d, out_axis, P, b_blk, ysh),
                  P.numel() * 4 + ysh.numel() * 2 + b_blk.numel() * 4),
-                ("bias_bwd", lambda: c3.virtual_cube_bias_bwd(d, gs, db), gs.numel() * 2 + q * q * Ns * 4)):
+                ("bias_bwd", lambda: c3.virtual_cube_bias_bwd(d, gs, db, db_ws), gs.numel() * 2 + q * q * Ns * 4)):
             fn()
             ms = timed(fn, 10)
             r[k] = {"avg_us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),

@@ -99,7 +99,8 @@ typedef enum cube3d_operand {
 typedef enum cube3d_op {
     CUBE3D_OP_FWD = 0,
     CUBE3D_OP_BWD_DX = 1,
-    CUBE3D_OP_BWD_DW = 2
+    CUBE3D_OP_BWD_DW = 2,
+    CUBE3D_OP_BIAS_BWD = 3  /* virtual_cube_bias_bwd (workspace query only) */
 } cube3d_op;
 
 /*
@@ -156,8 +157,9 @@ int cube3d_linear_bwd_dw(const cube3d_desc *desc, int i, int j, int l,
                          const void *X_block, const void *dY_block, void *R,
                          void *workspace, size_t workspace_bytes, void *stream);
 
-/* Scratch needed by a product call.  op is a cube3d_op; batched != 0 asks for
- * the all-processors launch.  Returns 0 for an invalid descriptor. */
+/* Scratch needed by a product call or by virtual_cube_bias_bwd.  op is a cube3d_op;
+ * batched != 0 asks for the all-processors launch (ignored for CUBE3D_OP_BIAS_BWD, which
+ * always covers the whole cube).  Returns 0 for an invalid descriptor. */
 size_t cube3d_workspace_bytes(const cube3d_desc *desc, int op, int batched);
 
 /*
@@ -222,14 +224,18 @@ int virtual_cube_assemble(const cube3d_desc *desc, int which,
  *   once to shard_dtype.  `axis` must be the output direction.
  * virtual_cube_bias_bwd: Algorithm 8: db = column sums of dY.  dY_shards: cube buffer of
  *   [Ms, Nb] in_dtype (fp8 codes are multiplied by scale_dy); dbias_diag: diagonal storage.
- *   The sums run over the rows in a fixed order in fp32 (run-to-run identical).  The printed
+ *   The sums run over the rows in a fixed order in fp32 (run-to-run identical), in two stages:
+ *   partial sums over groups of rows go to `workspace` (device memory, 16-byte aligned, at least
+ *   cube3d_workspace_bytes(desc, CUBE3D_OP_BIAS_BWD, 1) bytes, else CUBE3D_EWORKSPACE; contents
+ *   undefined afterwards), then the partials are added in ascending order.  The printed
  *   algorithm reduces along x only; the reduce along the output direction onto the diagonal
  *   (the adjoint of Algorithm 7's broadcast) is included, otherwise rows would be lost.
  */
 int virtual_cube_bias_gather(const cube3d_desc *desc, const void *bias_diag, void *bias_blocks, void *stream);
 int virtual_cube_reduce_scatter_bias(const cube3d_desc *desc, int axis, const void *partials, const void *bias_blocks,
                                      void *shards, void *stream);
-int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *stream);
+int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *workspace,
+                          size_t workspace_bytes, void *stream);
 
 const char *cube3d_status_string(int status);
 int cube3d_version(void);

@@ -15,7 +15,7 @@ OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH, ENOTIMPL = 0, -1, -2, -3, -4, -
 F32, BF16, FP8_E4M3 = 0, 1, 2
 AXIS_X, AXIS_Y, AXIS_Z = 0, 1, 2
 OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW, OPERAND_BIAS = range(7)
-OP_FWD, OP_BWD_DX, OP_BWD_DW = 0, 1, 2
+OP_FWD, OP_BWD_DX, OP_BWD_DW, OP_BIAS_BWD = 0, 1, 2, 3
 ALL_RANKS = (-1, -1, -1)
 
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "fp8_e4m3": FP8_E4M3}
@@ -80,7 +80,7 @@ def load():
     lib.virtual_cube_bias_gather.restype = ci
     lib.virtual_cube_reduce_scatter_bias.argtypes = [dp, ci, vp, vp, vp, vp]
     lib.virtual_cube_reduce_scatter_bias.restype = ci
-    lib.virtual_cube_bias_bwd.argtypes = [dp, vp, vp, vp]
+    lib.virtual_cube_bias_bwd.argtypes = [dp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.virtual_cube_bias_bwd.restype = ci
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
@@ -185,7 +185,8 @@ def virtual_cube_reduce_scatter_bias(desc, axis, partials, bias_blocks, shards, 
     return shards
 
 
-def virtual_cube_bias_bwd(desc, dY_shards, dbias_diag, stream=None):
-    _check(load().virtual_cube_bias_bwd(ctypes.byref(desc), _ptr(dY_shards), _ptr(dbias_diag), _stream(stream)),
-           "virtual_cube_bias_bwd")
+def virtual_cube_bias_bwd(desc, dY_shards, dbias_diag, workspace, stream=None):
+    _check(load().virtual_cube_bias_bwd(ctypes.byref(desc), _ptr(dY_shards), _ptr(dbias_diag), _ptr(workspace),
+                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                        _stream(stream)), "virtual_cube_bias_bwd")
     return dbias_diag

@@ -145,7 +145,9 @@ int cube3d_linear_bwd_dw(const cube3d_desc *desc, int i, int j, int l, const voi
 
 size_t cube3d_workspace_bytes(const cube3d_desc *desc, int op, int batched)
 {
-    if (check_desc(desc, nullptr) != CUBE3D_OK) return 0;
+    CubeGeom g;
+    if (check_desc(desc, &g) != CUBE3D_OK) return 0;
+    if (op == CUBE3D_OP_BIAS_BWD) return cube_bias_bwd_workspace(g, desc->in_dtype);
     GemmArgs a;
     const int batch = batched ? desc->q * desc->q * desc->q : 1;
     if (build_gemm(desc, op, batch, nullptr, nullptr, nullptr, nullptr, 0, nullptr, &a) != CUBE3D_OK) return 0;
@@ -212,14 +214,16 @@ int virtual_cube_bias_gather(const cube3d_desc *desc, const void *bias_diag, voi
                           static_cast<hipStream_t>(stream));
 }
 
-int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *stream)
+int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *workspace,
+                          size_t workspace_bytes, void *stream)
 {
     CubeGeom g;
     int rc = check_desc(desc, &g);
     if (rc != CUBE3D_OK) return rc;
-    if (!dY_shards || !dbias_diag || misaligned(dY_shards) || misaligned(dbias_diag)) return CUBE3D_EINVAL;
-    return cube_bias_bwd(g, desc->in_dtype, desc->scale_dy, dY_shards, static_cast<float *>(dbias_diag),
-                         static_cast<hipStream_t>(stream));
+    if (!dY_shards || !dbias_diag || misaligned(dY_shards) || misaligned(dbias_diag) || misaligned(workspace))
+        return CUBE3D_EINVAL;
+    return cube_bias_bwd(g, desc->in_dtype, desc->scale_dy, dY_shards, static_cast<float *>(dbias_diag), workspace,
+                         workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 static int storage_move(const cube3d_desc *desc, int which, bool scatter, const void *src, void *dst, void *stream)

@@ -342,52 +342,123 @@ template <> __device__ __forceinline__ float dy_value<unsigned char>(unsigned ch
     return (raw & 0x80) ? -mag : mag;
 }
 
-// One block per (diagonal processor (i, a, a), chunk of 64 of its Ns columns).  Lane = column;
-// the four wavefronts take the rows t = 4u + wave of the fixed sequence t = (i'*q + b')*Ms + row
-// over every processor (i', a, b') of the output block's column of the cube; each adds its rows
-// in ascending order, then the four sums are added in wavefront order.  Eight loads in flight.
-template <typename T>
-__global__ __launch_bounds__(256) void cube_bias_bwd_kernel(CubeGeom g, float scale, const T *__restrict__ dy,
-                                                            float *__restrict__ db)
+// Column sums of dY in two fixed-order stages (no atomics: every run adds in the same order).
+//
+// Stage 1: one block per (processor r, group of RG of its Ms rows, chunk of 64*V of its Nb columns).
+// A lane owns V consecutive columns (one 16-byte load per row when V > 1); the four wavefronts
+// take the rows 4u + wave of the group, eight rows in flight per wavefront, and add them in
+// ascending order; the four sums are then added in wavefront order and written to
+// part[(r * NRG + group) * Nb + column].
+template <typename T, int V>
+__global__ __launch_bounds__(256) void cube_bias_bwd_rows_kernel(CubeGeom g, int RG, int NRG,
+                                                                 const T *__restrict__ dy, float *__restrict__ part)
 {
-    __shared__ float part[4][64];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int i = blockIdx.x / g.q, a = blockIdx.x % g.q;
-    const int64_t c = (int64_t)blockIdx.y * 64 + lane;
-    const bool live = c < g.Ns;
-    const int64_t total = (int64_t)g.q * g.q * g.Ms;
-    float acc = 0.f;
+    __shared__ float lds[4][64 * V];
     constexpr int U = 8;
-    for (int64_t t0 = wave; t0 < total; t0 += 4 * U) {
-        float v[U];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int r = blockIdx.z, rg = blockIdx.y;
+    const int64_t c0 = ((int64_t)blockIdx.x * 64 + lane) * V;
+    const bool live = c0 < g.Nb;                       // Nb % V == 0: a lane is all in or all out
+    const int64_t row_lo = (int64_t)rg * RG, row_hi = row_lo + RG < g.Ms ? row_lo + RG : g.Ms;
+    const T *base = dy + ((int64_t)r * g.Ms) * g.Nb + c0;
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    for (int64_t t0 = row_lo + wave; t0 < row_hi; t0 += 4 * U) {
+        Pack<T, V> v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t t = t0 + 4 * u;
+            if (live && t < row_hi) v[u] = *reinterpret_cast<const Pack<T, V> *>(base + t * g.Nb);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (live && t0 + 4 * u < row_hi) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) acc[e] += dy_value<T>(v[u].v[e]);
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) lds[wave][e * 64 + lane] = acc[e];
+    __syncthreads();
+    float *out = part + ((int64_t)r * NRG + rg) * g.Nb + (int64_t)blockIdx.x * 64 * V;
+    for (int x = threadIdx.x; x < 64 * V; x += 256) {
+        const int ln = x / V, e = x % V;               // column x of the chunk sits at [e][ln]
+        if ((int64_t)blockIdx.x * 64 * V + x < g.Nb)
+            out[x] = ((lds[0][e * 64 + ln] + lds[1][e * 64 + ln]) + lds[2][e * 64 + ln]) + lds[3][e * 64 + ln];
+    }
+}
+
+// Stage 2: one block per (processor r, chunk of 64 of its Ns columns).  Processors off the diagonal
+// get zeros.  On the diagonal processor (i, a, a), lane = column; the terms t = (i'*q + b')*NRG + group
+// over every processor (i', a, b') of the output block's column of the cube are split into four
+// contiguous runs, one per wavefront, added in ascending order, and the four sums are added in
+// wavefront order: Algorithm 8's reduce along x plus the reduce along the output direction.
+__global__ __launch_bounds__(256) void cube_bias_bwd_finish_kernel(CubeGeom g, int NRG, float scale,
+                                                                   const float *__restrict__ part, float *__restrict__ db)
+{
+    __shared__ float lds[4][64];
+    constexpr int U = 8;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int r = blockIdx.x;
+    const int l = r % g.q, j = (r / g.q) % g.q, i = r / (g.q * g.q);
+    const int64_t c = (int64_t)blockIdx.y * 64 + lane;
+    const bool live = c < g.Ns;
+    if (j != l) {
+        if (wave == 0 && live) db[(int64_t)r * g.Ns + c] = 0.f;
+        return;
+    }
+    const int a = j;
+    const int total = g.q * g.q * NRG, per = (total + 3) / 4;
+    const int t_lo = wave * per, t_hi = t_lo + per < total ? t_lo + per : total;
+    float acc = 0.f;
+    for (int t0 = t_lo; t0 < t_hi; t0 += U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u;
             v[u] = 0.f;
-            if (live && t < total) {
-                const int64_t src_rank = t / g.Ms, row = t - src_rank * g.Ms;
-                const int i2 = (int)(src_rank / g.q), b2 = (int)(src_rank % g.q);
-                const int64_t rr = rank_index(g, i2, a, b2);
-                v[u] = dy_value<T>(dy[(rr * g.Ms + row) * g.Nb + (int64_t)i * g.Ns + c]);
+            if (live && t < t_hi) {
+                const int src = t / NRG, rg = t - src * NRG;
+                const int64_t rr = rank_index(g, src / g.q, a, src % g.q);
+                v[u] = part[(rr * NRG + rg) * g.Nb + (int64_t)i * g.Ns + c];
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) acc += v[u];
     }
-    part[wave][lane] = acc;
+    lds[wave][lane] = acc;
     __syncthreads();
-    if (wave == 0 && live) {
-        const float s = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
-        db[(((int64_t)i * g.q + a) * g.q + a) * g.Ns + c] = s * scale;
+    if (wave == 0 && live)
+        db[(int64_t)r * g.Ns + c] = (((lds[0][lane] + lds[1][lane]) + lds[2][lane]) + lds[3][lane]) * scale;
+}
+
+template <typename T>
+void launch_bias_bwd_rows(const CubeGeom &g, int RG, int NRG, const void *dy, float *part, hipStream_t stream)
+{
+    constexpr int V = 16 / (int)sizeof(T);
+    const unsigned nz = (unsigned)(g.q * g.q * g.q);
+    if (g.Nb % V == 0) {
+        dim3 grid((unsigned)((g.Nb + 64 * V - 1) / (64 * V)), (unsigned)NRG, nz);
+        hipLaunchKernelGGL((cube_bias_bwd_rows_kernel<T, V>), grid, dim3(256), 0, stream, g, RG, NRG,
+                           static_cast<const T *>(dy), part);
+    } else {
+        dim3 grid((unsigned)((g.Nb + 63) / 64), (unsigned)NRG, nz);
+        hipLaunchKernelGGL((cube_bias_bwd_rows_kernel<T, 1>), grid, dim3(256), 0, stream, g, RG, NRG,
+                           static_cast<const T *>(dy), part);
     }
 }
 
-__global__ __launch_bounds__(256) void cube_bias_zero_offdiag_kernel(CubeGeom g, float *__restrict__ db)
+// Rows per stage-1 block: as many as keep at least ~2048 blocks in flight (8 per compute unit),
+// between 16 and 256, a power of two; depends on the shape only.
+int bias_bwd_row_group(const CubeGeom &g, int es)
 {
-    const int r = blockIdx.x;
-    const int l = r % g.q, j = (r / g.q) % g.q;
-    if (j == l) return;
-    for (int64_t e = threadIdx.x; e < g.Ns; e += 256) db[(int64_t)r * g.Ns + e] = 0.f;
+    const int V = g.Nb % (16 / es) == 0 ? 16 / es : 1;
+    const int64_t chunks = (g.Nb + 64 * V - 1) / (64 * V) * (int64_t)g.q * g.q * g.q;
+    int RG = 256;
+    while (RG > 16 && chunks * ((g.Ms + RG - 1) / RG) < 2048) RG /= 2;
+    return RG;
 }
 
 }  // namespace
@@ -399,27 +470,32 @@ int cube_bias_move(const CubeGeom &g, int mode, const float *src, float *dst, hi
     return launch_status();
 }
 
-int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *dy_shards, float *dbias_diag,
-                  hipStream_t stream)
+size_t cube_bias_bwd_workspace(const CubeGeom &g, int dy_dtype)
 {
-    dim3 grid((unsigned)(g.q * g.q), (unsigned)((g.Ns + 63) / 64), 1);
-    if (grid.y > 65535) return CUBE3D_ESHAPE;
-    hipLaunchKernelGGL(cube_bias_zero_offdiag_kernel, dim3((unsigned)(g.q * g.q * g.q)), dim3(256), 0, stream, g, dbias_diag);
+    const int es = dy_dtype == CUBE3D_F32 ? 4 : dy_dtype == CUBE3D_BF16 ? 2 : 1;
+    const int RG = bias_bwd_row_group(g, es);
+    const int64_t NRG = (g.Ms + RG - 1) / RG;
+    return (size_t)((int64_t)g.q * g.q * g.q * NRG * g.Nb) * sizeof(float);
+}
+
+int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *dy_shards, float *dbias_diag,
+                  void *workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    if (dy_dtype != CUBE3D_F32 && dy_dtype != CUBE3D_BF16 && dy_dtype != CUBE3D_FP8_E4M3) return CUBE3D_EDTYPE;
+    const int es = dy_dtype == CUBE3D_F32 ? 4 : dy_dtype == CUBE3D_BF16 ? 2 : 1;
+    const int RG = bias_bwd_row_group(g, es);
+    const int NRG = (int)((g.Ms + RG - 1) / RG);
+    if (NRG > 65535 || (g.Ns + 63) / 64 > 65535 || (int64_t)g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;
+    if (!workspace || workspace_bytes < cube_bias_bwd_workspace(g, dy_dtype)) return CUBE3D_EWORKSPACE;
+    float *part = static_cast<float *>(workspace);
     switch (dy_dtype) {
-    case CUBE3D_F32:
-        hipLaunchKernelGGL((cube_bias_bwd_kernel<float>), grid, dim3(256), 0, stream, g, 1.f,
-                           static_cast<const float *>(dy_shards), dbias_diag);
-        break;
-    case CUBE3D_BF16:
-        hipLaunchKernelGGL((cube_bias_bwd_kernel<unsigned short>), grid, dim3(256), 0, stream, g, 1.f,
-                           static_cast<const unsigned short *>(dy_shards), dbias_diag);
-        break;
-    case CUBE3D_FP8_E4M3:
-        hipLaunchKernelGGL((cube_bias_bwd_kernel<unsigned char>), grid, dim3(256), 0, stream, g, scale_dy,
-                           static_cast<const unsigned char *>(dy_shards), dbias_diag);
-        break;
-    default: return CUBE3D_EDTYPE;
+    case CUBE3D_F32: launch_bias_bwd_rows<float>(g, RG, NRG, dy_shards, part, stream); break;
+    case CUBE3D_BF16: launch_bias_bwd_rows<unsigned short>(g, RG, NRG, dy_shards, part, stream); break;
+    default: launch_bias_bwd_rows<unsigned char>(g, RG, NRG, dy_shards, part, stream); break;
     }
+    dim3 grid2((unsigned)(g.q * g.q * g.q), (unsigned)((g.Ns + 63) / 64), 1);
+    hipLaunchKernelGGL(cube_bias_bwd_finish_kernel, grid2, dim3(256), 0, stream, g, NRG,
+                       dy_dtype == CUBE3D_FP8_E4M3 ? scale_dy : 1.f, part, dbias_diag);
     return launch_status();
 }
 

@@ -75,8 +75,10 @@ int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, h
 int cube_reduce(const CubeGeom &g, int mode, int partial_dtype, int shard_dtype, const void *partials, void *shards,
                 const float *bias, hipStream_t stream);
 int cube_bias_move(const CubeGeom &g, int mode, const float *src, float *dst, hipStream_t stream);
+// fp32 partial column sums of the two-stage bias gradient (bytes); depends on the shape only
+size_t cube_bias_bwd_workspace(const CubeGeom &g, int dy_dtype);
 int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *dy_shards, float *dbias_diag,
-                  hipStream_t stream);
+                  void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 inline int launch_status()
 {

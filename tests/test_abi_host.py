@@ -122,9 +122,15 @@ def test_bias_argument_errors(lib):
     assert r(ctypes.byref(d), c3.AXIS_Z, FAKE, None, FAKE, None) == c3.EINVAL
     assert r(ctypes.byref(d), c3.AXIS_Z, None, FAKE, FAKE, None) == c3.EINVAL
     assert r(ctypes.byref(good(in_axis=c3.AXIS_Z)), c3.AXIS_Z, FAKE, FAKE, FAKE, None) == c3.EINVAL
-    assert b(ctypes.byref(d), None, FAKE, None) == c3.EINVAL
-    assert b(ctypes.byref(d), FAKE, ODD, None) == c3.EINVAL
-    assert b(ctypes.byref(good(in_dtype=11)), FAKE, FAKE, None) == c3.EDTYPE
+    need = c3.cube3d_workspace_bytes(d, c3.OP_BIAS_BWD, True)
+    assert need >= d.q ** 3 * (d.N // d.q) * 4          # at least one fp32 row of partials per processor
+    assert need == c3.cube3d_workspace_bytes(d, c3.OP_BIAS_BWD, False)
+    assert b(ctypes.byref(d), None, FAKE, FAKE, need, None) == c3.EINVAL
+    assert b(ctypes.byref(d), FAKE, ODD, FAKE, need, None) == c3.EINVAL
+    assert b(ctypes.byref(d), FAKE, FAKE, ODD, need, None) == c3.EINVAL
+    assert b(ctypes.byref(good(in_dtype=11)), FAKE, FAKE, FAKE, need, None) == c3.EDTYPE
+    assert b(ctypes.byref(d), FAKE, FAKE, None, 0, None) == c3.EWORKSPACE
+    assert b(ctypes.byref(d), FAKE, FAKE, FAKE, need - 1, None) == c3.EWORKSPACE
     for f in (lib.virtual_cube_scatter, lib.virtual_cube_assemble):
         assert f(ctypes.byref(d), c3.OPERAND_BIAS, None, FAKE, None) == c3.EINVAL
 

@@ -363,7 +363,7 @@ def run_bias(q, M, K, N, dtype, dist, seed, ax):
     c3.virtual_cube_assemble(d, c3.OPERAND_Y, ys, Yf)
     # gradient of the bias from the dY shards
     db_diag = gu.empty((n, cube.Ns), "f32")
-    c3.virtual_cube_bias_bwd(d, gs, db_diag)
+    c3.virtual_cube_bias_bwd(d, gs, db_diag, gu.workspace(d, c3.OP_BIAS_BWD, True))
     db_full = gu.empty((N,), "f32")
     c3.virtual_cube_assemble(d, c3.OPERAND_BIAS, db_diag, db_full)
     torch.cuda.synchronize()
@@ -382,7 +382,7 @@ def run_bias(q, M, K, N, dtype, dist, seed, ax):
         assert gu.scaled_max_err(db_full.cpu().numpy().astype(np.float64), val["dY"].sum(axis=0)) <= 1e-4
     # deterministic: a second run gives the same bits
     db2 = gu.empty((n, cube.Ns), "f32")
-    c3.virtual_cube_bias_bwd(d, gs, db2)
+    c3.virtual_cube_bias_bwd(d, gs, db2, gu.workspace(d, c3.OP_BIAS_BWD, True))
     torch.cuda.synchronize()
     assert np.array_equal(db2.cpu().numpy(), db_diag.cpu().numpy())
 
