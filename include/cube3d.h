@@ -237,6 +237,32 @@ int virtual_cube_reduce_scatter_bias(const cube3d_desc *desc, int axis, const vo
 int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *dbias_diag, void *workspace,
                           size_t workspace_bytes, void *stream);
 
+/*
+ * The whole virtual cube in one product, shards read and written in place.  On one GPU all
+ * q^3 processors' shards share one memory, so the collectives of Algorithms 1 and 2 need not
+ * move data: the all-gathers (Algorithm 1 steps 1-2, and of dY in Algorithm 2) become address
+ * arithmetic on the shards (Section 3.1.1 fixes where every index lives), and the reduce-scatter's
+ * sum over the q partial products is the K loop running on across the shards of the contraction
+ * index, so each output element is accumulated in fp32 over the full contraction and rounded
+ * once to shard_dtype (desc->out_dtype is not used).  Results equal those of gather -> product
+ * -> reduce-scatter up to fp32 summation order (bit for bit on small-integer data).
+ *   fwd:     X_shards cube of [Ms, Kb], W_shards cube of [Kb, Ns] (in_dtype) -> Y_shards cube of
+ *            [Ms, Nb] (shard_dtype); bias_diag: NULL, or the diagonal storage of b (fp32), then
+ *            Y = X W + b (Algorithm 7 folded into the store).
+ *   bwd_dx:  dY_shards [Ms, Nb], W_shards [Kb, Ns] -> dX_shards [Ms, Kb]   (Algorithm 2 line 1)
+ *   bwd_dw:  X_shards [Ms, Kb], dY_shards [Ms, Nb] -> dW_shards [Kb, Ns]   (Algorithm 2 line 2)
+ * fp8 inputs are scaled by the product of the two operand scales.  Needs no workspace.
+ * Any valid descriptor is accepted; shapes that fit the tuned kernel's tiles (all of M, K, N
+ * multiples of 128, shard sizes multiples of 32, bf16 or fp8 inputs) run on it, the rest on the
+ * bounds-checked kernel.
+ */
+int virtual_cube_linear_fwd(const cube3d_desc *desc, const void *X_shards, const void *W_shards, const void *bias_diag,
+                            void *Y_shards, void *stream);
+int virtual_cube_linear_bwd_dx(const cube3d_desc *desc, const void *dY_shards, const void *W_shards, void *dX_shards,
+                               void *stream);
+int virtual_cube_linear_bwd_dw(const cube3d_desc *desc, const void *X_shards, const void *dY_shards, void *dW_shards,
+                               void *stream);
+
 const char *cube3d_status_string(int status);
 int cube3d_version(void);
 

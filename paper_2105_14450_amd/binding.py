@@ -82,6 +82,12 @@ def load():
     lib.virtual_cube_reduce_scatter_bias.restype = ci
     lib.virtual_cube_bias_bwd.argtypes = [dp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.virtual_cube_bias_bwd.restype = ci
+    lib.virtual_cube_linear_fwd.argtypes = [dp, vp, vp, vp, vp, vp]
+    lib.virtual_cube_linear_fwd.restype = ci
+    lib.virtual_cube_linear_bwd_dx.argtypes = [dp, vp, vp, vp, vp]
+    lib.virtual_cube_linear_bwd_dx.restype = ci
+    lib.virtual_cube_linear_bwd_dw.argtypes = [dp, vp, vp, vp, vp]
+    lib.virtual_cube_linear_bwd_dw.restype = ci
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
     lib.cube3d_version.restype = ci
@@ -92,7 +98,8 @@ def load():
 EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", "cube3d_workspace_bytes",
            "virtual_cube_gather", "virtual_cube_reduce_scatter", "virtual_cube_scatter",
            "virtual_cube_assemble", "virtual_cube_bias_gather", "virtual_cube_reduce_scatter_bias",
-           "virtual_cube_bias_bwd", "cube3d_status_string", "cube3d_version")
+           "virtual_cube_bias_bwd", "virtual_cube_linear_fwd", "virtual_cube_linear_bwd_dx",
+           "virtual_cube_linear_bwd_dw", "cube3d_status_string", "cube3d_version")
 
 
 def status_string(status: int) -> str:
@@ -190,3 +197,21 @@ def virtual_cube_bias_bwd(desc, dY_shards, dbias_diag, workspace, stream=None):
                                         0 if workspace is None else workspace.numel() * workspace.element_size(),
                                         _stream(stream)), "virtual_cube_bias_bwd")
     return dbias_diag
+
+
+def virtual_cube_linear_fwd(desc, X_shards, W_shards, bias_diag, Y_shards, stream=None):
+    _check(load().virtual_cube_linear_fwd(ctypes.byref(desc), _ptr(X_shards), _ptr(W_shards), _ptr(bias_diag),
+                                          _ptr(Y_shards), _stream(stream)), "virtual_cube_linear_fwd")
+    return Y_shards
+
+
+def virtual_cube_linear_bwd_dx(desc, dY_shards, W_shards, dX_shards, stream=None):
+    _check(load().virtual_cube_linear_bwd_dx(ctypes.byref(desc), _ptr(dY_shards), _ptr(W_shards), _ptr(dX_shards),
+                                             _stream(stream)), "virtual_cube_linear_bwd_dx")
+    return dX_shards
+
+
+def virtual_cube_linear_bwd_dw(desc, X_shards, dY_shards, dW_shards, stream=None):
+    _check(load().virtual_cube_linear_bwd_dw(ctypes.byref(desc), _ptr(X_shards), _ptr(dY_shards), _ptr(dW_shards),
+                                             _stream(stream)), "virtual_cube_linear_bwd_dw")
+    return dW_shards

@@ -121,6 +121,78 @@ int run_product(const cube3d_desc *d, int op, int i, int j, int l, const void *A
     return gemm_generic(a);
 }
 
+// Where the indices of the full matrices land in the cube buffers of shards (Section 3.1.1):
+//   X shard of (i, a, b) = X[i*Mb + a*Ms : +Ms, b*Kb : +Kb]               stored [Ms, Kb]
+//   W shard of (i, a, b) = W[b*Kb : +Kb, a*Nb + i*Ns : +Ns]               stored [Kb, Ns]
+//   Y shard of (i, a, b) = Y[i*Mb + b*Ms : +Ms, a*Nb : +Nb]               stored [Ms, Nb]
+//   bias on (i, a, a)    = b[a*Nb + i*Ns : +Ns]
+// with (a, b) the processor's indices along the input / output direction.
+struct ShardMaps {
+    AxisMap xm, xk, wk, wn, ym, yn, bn;
+};
+
+ShardMaps shard_maps(const CubeGeom &g)
+{
+    const int64_t Ri = (int64_t)g.q * g.q, Ra = g.in_axis_z ? 1 : g.q, Rb = g.in_axis_z ? g.q : 1;
+    const int64_t xs = g.Ms * g.Kb, ws = g.Kb * g.Ns, ys = g.Ms * g.Nb;
+    ShardMaps m;
+    m.xm = AxisMap{(int32_t)g.Mb, (int32_t)g.Ms, Ri * xs, Ra * xs, g.Kb};
+    m.xk = AxisMap{(int32_t)g.Kb, (int32_t)g.Kb, Rb * xs, 0, 1};
+    m.wk = AxisMap{(int32_t)g.Kb, (int32_t)g.Kb, Rb * ws, 0, g.Ns};
+    m.wn = AxisMap{(int32_t)g.Nb, (int32_t)g.Ns, Ra * ws, Ri * ws, 1};
+    m.ym = AxisMap{(int32_t)g.Mb, (int32_t)g.Ms, Ri * ys, Rb * ys, g.Nb};
+    m.yn = AxisMap{(int32_t)g.Nb, (int32_t)g.Nb, Ra * ys, 0, 1};
+    m.bn = AxisMap{(int32_t)g.Nb, (int32_t)g.Ns, (Ra + Rb) * g.Ns, Ri * g.Ns, 1};
+    return m;
+}
+
+// One product over the whole cube with the shards read and written in place.
+int run_cube_product(const cube3d_desc *d, int op, const void *A, const void *B, const void *bias, void *C, void *stream)
+{
+    CubeGeom g;
+    int rc = check_desc(d, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!A || !B || !C || misaligned(A) || misaligned(B) || misaligned(C) || misaligned(bias)) return CUBE3D_EINVAL;
+    if (g.M >= (1ll << 31) || g.K >= (1ll << 31) || g.N >= (1ll << 31)) return CUBE3D_ESHAPE;
+    const ShardMaps sm = shard_maps(g);
+    const bool fp8 = d->in_dtype == CUBE3D_FP8_E4M3;
+    GemmMaps mp{};
+    GemmArgs a{};
+    a.A = A; a.B = B; a.C = C;
+    a.batch = 1;
+    a.in_dtype = d->in_dtype;
+    a.out_dtype = d->shard_dtype;
+    a.stream = static_cast<hipStream_t>(stream);
+    switch (op) {
+    case CUBE3D_OP_FWD:      // Y[M,N] = X[M,K] W[K,N] (+ b)
+        a.Mo = g.M; a.No = g.N; a.Kc = g.K;
+        a.a_kmajor = true; a.b_kmajor = false;
+        mp.a_mn = sm.xm; mp.a_k = sm.xk; mp.b_mn = sm.wn; mp.b_k = sm.wk; mp.c_m = sm.ym; mp.c_n = sm.yn;
+        mp.bias = static_cast<const float *>(bias);
+        mp.bias_n = sm.bn;
+        a.alpha = fp8 ? d->scale_x * d->scale_w : 1.f;
+        break;
+    case CUBE3D_OP_BWD_DX:   // dX[M,K] = dY[M,N] W[K,N]^T
+        a.Mo = g.M; a.No = g.K; a.Kc = g.N;
+        a.a_kmajor = true; a.b_kmajor = true;
+        mp.a_mn = sm.ym; mp.a_k = sm.yn; mp.b_mn = sm.wk; mp.b_k = sm.wn; mp.c_m = sm.xm; mp.c_n = sm.xk;
+        a.alpha = fp8 ? d->scale_dy * d->scale_w : 1.f;
+        break;
+    case CUBE3D_OP_BWD_DW:   // dW[K,N] = X[M,K]^T dY[M,N]
+        a.Mo = g.K; a.No = g.N; a.Kc = g.M;
+        a.a_kmajor = false; a.b_kmajor = false;
+        mp.a_mn = sm.xk; mp.a_k = sm.xm; mp.b_mn = sm.yn; mp.b_k = sm.ym; mp.c_m = sm.wk; mp.c_n = sm.wn;
+        a.alpha = fp8 ? d->scale_x * d->scale_dy : 1.f;
+        break;
+    default: return CUBE3D_EINVAL;
+    }
+    if (mp.bias == nullptr) mp.bias_n = sm.bn;
+    a.maps = &mp;
+    rc = gemm_fast(a);
+    if (rc != CUBE3D_ENOTIMPL) return rc;
+    return gemm_generic(a);
+}
+
 }  // namespace
 
 extern "C" {
@@ -224,6 +296,24 @@ int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *
         return CUBE3D_EINVAL;
     return cube_bias_bwd(g, desc->in_dtype, desc->scale_dy, dY_shards, static_cast<float *>(dbias_diag), workspace,
                          workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_linear_fwd(const cube3d_desc *desc, const void *X_shards, const void *W_shards, const void *bias_diag,
+                            void *Y_shards, void *stream)
+{
+    return run_cube_product(desc, CUBE3D_OP_FWD, X_shards, W_shards, bias_diag, Y_shards, stream);
+}
+
+int virtual_cube_linear_bwd_dx(const cube3d_desc *desc, const void *dY_shards, const void *W_shards, void *dX_shards,
+                               void *stream)
+{
+    return run_cube_product(desc, CUBE3D_OP_BWD_DX, dY_shards, W_shards, nullptr, dX_shards, stream);
+}
+
+int virtual_cube_linear_bwd_dw(const cube3d_desc *desc, const void *X_shards, const void *dY_shards, void *dW_shards,
+                               void *stream)
+{
+    return run_cube_product(desc, CUBE3D_OP_BWD_DW, X_shards, dY_shards, nullptr, dW_shards, stream);
 }
 
 static int storage_move(const cube3d_desc *desc, int which, bool scatter, const void *src, void *dst, void *stream)

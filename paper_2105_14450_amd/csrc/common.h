@@ -15,6 +15,33 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 
+// Piecewise-linear placement of one matrix index in memory, two panel levels deep:
+//   offset(x) = (x / P1) * s1 + ((x % P1) / P2) * s2 + (x % P2) * u        (elements)
+// with P2 dividing P1.  It describes how a row or column index of a full matrix lands in a
+// cube buffer of shards (Section 3.1.1): P1 = block size, P2 = shard size, s1 / s2 = distances
+// between the processors that hold consecutive blocks / shards, u = distance inside a shard.
+// An index that is split once uses P2 = P1, s2 = 0.
+struct AxisMap {
+    int32_t P1, P2;
+    int64_t s1, s2, u;
+};
+
+__host__ __device__ __forceinline__ int64_t axis_offset(const AxisMap &m, int64_t x)
+{
+    const uint32_t xx = (uint32_t)x;
+    const uint32_t hi = xx / (uint32_t)m.P1, r1 = xx - hi * (uint32_t)m.P1;
+    const uint32_t mid = r1 / (uint32_t)m.P2, lo = r1 - mid * (uint32_t)m.P2;
+    return (int64_t)hi * m.s1 + (int64_t)mid * m.s2 + (int64_t)lo * m.u;
+}
+
+// Element (mn, k) of operand A sits at A[a_mn(mn) + a_k(k)], of B at B[b_mn(mn) + b_k(k)];
+// output element (m, n) at C[c_m(m) + c_n(n)].  bias (optional, fp32) is indexed by bias_n(n)
+// and added to the scaled accumulator before the store.
+struct GemmMaps {
+    AxisMap a_mn, a_k, b_mn, b_k, c_m, c_n, bias_n;
+    const float *bias;
+};
+
 // One (possibly batched) product  C[Mo,No] = alpha * opA * opB  with fp32 accumulation.
 //   a_kmajor: A is stored [Mo, Kc] (contraction index contiguous), else [Kc, Mo]
 //   b_kmajor: B is stored [No, Kc] (contraction index contiguous), else [Kc, No]
@@ -36,6 +63,9 @@ struct GemmArgs {
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;
+    // nullptr: plain row-major operands (lda / ldb / ldc).  Otherwise the operands and the output
+    // are addressed through these maps (batch must be 1; leading dimensions and strides unused).
+    const GemmMaps *maps;
 };
 
 // Any shape, any supported dtype; bounds-checked.  Returns a cube3d_status.
@@ -44,6 +74,8 @@ int gemm_generic(const GemmArgs &g);
 // Tuned bf16 / fp8 path; returns CUBE3D_ENOTIMPL when the shape does not fit its tiles.
 int gemm_fast(const GemmArgs &g);
 size_t gemm_fast_workspace(const GemmArgs &g);
+// Launch of the tuned kernel's map-addressed instantiations (tile = 256 or 128, chosen by gemm_fast).
+int gemm_fast_mapped(const GemmArgs &g, int tile);
 
 // Geometry of the virtual cube and the data-movement kernels over it.
 struct CubeGeom {

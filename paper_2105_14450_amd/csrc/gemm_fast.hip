@@ -15,6 +15,18 @@ struct Plan {
     int splits;
 };
 
+// What the map-addressed instantiations assume of an index placement.
+//   walked (the contraction index): a K-tile of `kpt` indices never straddles a shard
+//   contiguous: the index that is contiguous in memory moves in 16-byte pieces of `piece` elements
+//   rows: a run of `run` consecutive indices (a load chunk, an output strip) lies in one shard
+bool map_ok(const AxisMap &m, int64_t extent, int64_t stride_align, bool contiguous, int64_t granule)
+{
+    if (m.P1 <= 0 || m.P2 <= 0 || m.P1 % m.P2 || extent % m.P1) return false;
+    if (m.P2 % granule) return false;
+    if (contiguous ? m.u != 1 : m.u % stride_align != 0) return false;
+    return m.s1 % stride_align == 0 && m.s2 % stride_align == 0;
+}
+
 // Pure function of the shape, so that cube3d_workspace_bytes() and the launch agree.
 Plan make_plan(const GemmArgs &g)
 {
@@ -23,6 +35,23 @@ Plan make_plan(const GemmArgs &g)
     if (g.in_dtype != CUBE3D_BF16 && !fp8) return p;
     const int es = fp8 ? 1 : 2;
     const int64_t align = 16 / es;              // operands are moved in 16-byte pieces
+    if (g.maps) {
+        // a cube of shards read in place: one product over the whole cube, no split-K
+        if (g.batch != 1 || g.Mo >= (1ll << 31) || g.No >= (1ll << 31) || g.Kc >= (1ll << 31)) return p;
+        if (g.out_dtype != CUBE3D_F32 && g.out_dtype != CUBE3D_BF16) return p;
+        const GemmMaps &m = *g.maps;
+        const int64_t kpt = 64 / es;            // contraction indices per 64-byte K-tile
+        const int64_t oalign = g.out_dtype == CUBE3D_F32 ? 4 : 8;
+        if (!map_ok(m.a_k, g.Kc, align, g.a_kmajor, kpt) || !map_ok(m.b_k, g.Kc, align, g.b_kmajor, kpt)) return p;
+        if (!map_ok(m.a_mn, g.Mo, align, !g.a_kmajor, 16) || !map_ok(m.b_mn, g.No, align, !g.b_kmajor, 16)) return p;
+        if (!map_ok(m.c_m, g.Mo, oalign, false, 32) || !map_ok(m.c_n, g.No, oalign, true, oalign)) return p;
+        if (m.bias && !map_ok(m.bias_n, g.No, 1, true, 4)) return p;
+        if (g.Kc % (fp8 ? 2 * kpt : kpt) || g.Kc < (fp8 ? 2 * kpt : kpt)) return p;   // fp8 K-tiles go in pairs
+        const bool f256 = g.Mo % 256 == 0 && g.No % 256 == 0, f128 = !fp8 && g.Mo % 128 == 0 && g.No % 128 == 0;
+        if (!f256 && !f128) return p;
+        p.tile = (f256 && ((g.Mo / 256) * (g.No / 256) >= (3 * NUM_CU) / 4 || !f128)) ? 256 : 128;
+        return p;
+    }
     if (g.lda % align || g.ldb % align || g.strideA % align || g.strideB % align) return p;
     if (g.ldc % 8 || g.strideC % 8) return p;
     if (g.batch > 16384) return p;
@@ -114,6 +143,7 @@ int gemm_fast(const GemmArgs &g)
 {
     const Plan pl = make_plan(g);
     if (pl.tile == 0) return CUBE3D_ENOTIMPL;
+    if (g.maps) return gemm_fast_mapped(g, pl.tile);
     const bool f32 = g.out_dtype == CUBE3D_F32;
     if (g.in_dtype == CUBE3D_FP8_E4M3)
         return f32 ? run_tile<Fp8, 256, float>(g, pl) : run_tile<Fp8, 256, unsigned short>(g, pl);

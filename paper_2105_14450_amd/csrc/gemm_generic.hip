@@ -58,12 +58,23 @@ template <> __device__ __forceinline__ void store_out<unsigned short>(unsigned s
     *p = f32_to_bf16_bits(v);
 }
 
-template <typename TIn, typename TOut, bool AK, bool BK>
+// MAPPED: every element address goes through the index maps (operands and output are cubes of
+// shards, Section 3.1.1) and the optional bias is added; the leading dimensions are unused.
+template <typename TIn, typename TOut, bool AK, bool BK, bool MAPPED>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const TIn *__restrict__ A, const TIn *__restrict__ B,
                                                            TOut *__restrict__ C, int64_t Mo, int64_t No, int64_t Kc,
                                                            int64_t lda, int64_t ldb, int64_t ldc, int64_t sA,
-                                                           int64_t sB, int64_t sC, float alpha)
+                                                           int64_t sB, int64_t sC, float alpha, GemmMaps maps)
 {
+    // address of operand element (mn, k): plain leading dimension, or the two index maps
+    auto a_at = [&](int64_t gm, int64_t gk) -> int64_t {
+        if (MAPPED) return axis_offset(maps.a_mn, gm) + axis_offset(maps.a_k, gk);
+        return AK ? gm * lda + gk : gk * lda + gm;
+    };
+    auto b_at = [&](int64_t gn, int64_t gk) -> int64_t {
+        if (MAPPED) return axis_offset(maps.b_mn, gn) + axis_offset(maps.b_k, gk);
+        return BK ? gn * ldb + gk : gk * ldb + gn;
+    };
     constexpr int LD = TK + Elem<TIn>::PAD;
     __shared__ __attribute__((aligned(16))) TIn As[TM * LD];
     __shared__ __attribute__((aligned(16))) TIn Bs[TN * LD];
@@ -91,26 +102,26 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const TIn *__restrict
             const int k = tid & 31;
             for (int r = tid >> 5; r < TM; r += 8) {
                 const int64_t gm = m0 + r, gk = k0 + k;
-                As[r * LD + k] = (gm < Mo && gk < Kc) ? A[gm * lda + gk] : TIn(0);
+                As[r * LD + k] = (gm < Mo && gk < Kc) ? A[a_at(gm, gk)] : TIn(0);
             }
         } else {
             const int r = tid & 63;
             for (int k = tid >> 6; k < TK; k += 4) {
                 const int64_t gm = m0 + r, gk = k0 + k;
-                As[r * LD + k] = (gm < Mo && gk < Kc) ? A[gk * lda + gm] : TIn(0);
+                As[r * LD + k] = (gm < Mo && gk < Kc) ? A[a_at(gm, gk)] : TIn(0);
             }
         }
         if (BK) {
             const int k = tid & 31;
             for (int r = tid >> 5; r < TN; r += 8) {
                 const int64_t gn = n0 + r, gk = k0 + k;
-                Bs[r * LD + k] = (gn < No && gk < Kc) ? B[gn * ldb + gk] : TIn(0);
+                Bs[r * LD + k] = (gn < No && gk < Kc) ? B[b_at(gn, gk)] : TIn(0);
             }
         } else {
             const int r = tid & 63;
             for (int k = tid >> 6; k < TK; k += 4) {
                 const int64_t gn = n0 + r, gk = k0 + k;
-                Bs[r * LD + k] = (gn < No && gk < Kc) ? B[gk * ldb + gn] : TIn(0);
+                Bs[r * LD + k] = (gn < No && gk < Kc) ? B[b_at(gn, gk)] : TIn(0);
             }
         }
         __syncthreads();
@@ -122,10 +133,15 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const TIn *__restrict
     // 32x32 accumulator: register v of lane holds row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
     const int64_t col = n0 + wn + (lane & 31);
     if (col < No) {
+        const float bias = (MAPPED && maps.bias) ? maps.bias[axis_offset(maps.bias_n, col)] : 0.f;
+        const int64_t col_off = MAPPED ? axis_offset(maps.c_n, col) : col;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int64_t row = m0 + wm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (row < Mo) store_out<TOut>(C + row * ldc + col, acc[v] * alpha);
+            if (row < Mo) {
+                const int64_t row_off = MAPPED ? axis_offset(maps.c_m, row) : row * ldc;
+                store_out<TOut>(C + row_off + col_off, MAPPED ? acc[v] * alpha + bias : acc[v] * alpha);
+            }
         }
     }
 }
@@ -138,13 +154,20 @@ int launch_layout(const GemmArgs &g)
     const TIn *A = static_cast<const TIn *>(g.A);
     const TIn *B = static_cast<const TIn *>(g.B);
     TOut *C = static_cast<TOut *>(g.C);
-#define CUBE3D_LAUNCH(AKV, BKV)                                                                               \
-    hipLaunchKernelGGL((gemm_generic_kernel<TIn, TOut, AKV, BKV>), grid, block, 0, g.stream, A, B, C, g.Mo, \
-                       g.No, g.Kc, g.lda, g.ldb, g.ldc, g.strideA, g.strideB, g.strideC, g.alpha)
-    if (g.a_kmajor && g.b_kmajor) CUBE3D_LAUNCH(true, true);
-    else if (g.a_kmajor && !g.b_kmajor) CUBE3D_LAUNCH(true, false);
-    else if (!g.a_kmajor && !g.b_kmajor) CUBE3D_LAUNCH(false, false);
-    else CUBE3D_LAUNCH(false, true);
+    const GemmMaps maps = g.maps ? *g.maps : GemmMaps{};
+#define CUBE3D_LAUNCH(AKV, BKV, MP)                                                                               \
+    hipLaunchKernelGGL((gemm_generic_kernel<TIn, TOut, AKV, BKV, MP>), grid, block, 0, g.stream, A, B, C, g.Mo, \
+                       g.No, g.Kc, g.lda, g.ldb, g.ldc, g.strideA, g.strideB, g.strideC, g.alpha, maps)
+    if (g.maps) {
+        if (g.batch != 1) return CUBE3D_EINVAL;
+        if (g.a_kmajor && g.b_kmajor) CUBE3D_LAUNCH(true, true, true);
+        else if (g.a_kmajor && !g.b_kmajor) CUBE3D_LAUNCH(true, false, true);
+        else if (!g.a_kmajor && !g.b_kmajor) CUBE3D_LAUNCH(false, false, true);
+        else return CUBE3D_ENOTIMPL;
+    } else if (g.a_kmajor && g.b_kmajor) CUBE3D_LAUNCH(true, true, false);
+    else if (g.a_kmajor && !g.b_kmajor) CUBE3D_LAUNCH(true, false, false);
+    else if (!g.a_kmajor && !g.b_kmajor) CUBE3D_LAUNCH(false, false, false);
+    else CUBE3D_LAUNCH(false, true, false);
 #undef CUBE3D_LAUNCH
     return launch_status();
 }

@@ -182,6 +182,25 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
     return (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16);
 }
 
+// Advance of a map-addressed operand from one K-tile to the next (all values in elements): the
+// plain step inside a shard, and the corrections when the tile walks off a shard (jump2) or off
+// a block (jump1) of the contraction index.
+struct KWalk {
+    int64_t step, jump1, jump2;
+    int32_t P1, P2;
+};
+
+inline KWalk make_kwalk(const AxisMap &m, int k_per_tile)
+{
+    KWalk w;
+    w.step = (int64_t)k_per_tile * m.u;
+    w.jump2 = m.s2 - (int64_t)m.P2 * m.u;
+    w.jump1 = m.s1 - (int64_t)m.P2 * m.u - (int64_t)(m.P1 / m.P2 - 1) * m.s2;
+    w.P1 = m.P1;
+    w.P2 = m.P2;
+    return w;
+}
+
 struct Params {
     const void *A;
     const void *B;
@@ -193,10 +212,14 @@ struct Params {
     int splits;                 // split-K: blockIdx.y = batch * splits + split; split s takes K-tiles [s*nk, (s+1)*nk)
     int64_t sSplit;             // output distance between the partial results of consecutive splits (elements)
     float alpha;
+    // MAPPED instantiations only (then lda / ldb / ldc, the strides and the splits are unused)
+    GemmMaps maps;
+    KWalk ka, kb;
 };
 
-// TOut: float or unsigned short (bf16 bits)
-template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut>
+// TOut: float or unsigned short (bf16 bits).  MAPPED: operands, output and the optional bias are
+// addressed through p.maps (a cube of shards read in place) instead of leading dimensions.
+template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut, bool MAPPED = false>
 __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma_kernel(const Params p)
 {
     typedef typename E::Elem Elem;
@@ -225,7 +248,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     static_assert(NSTAGE >= 2, "at least double buffering");
     static_assert(!TWO_STAGE || KS % 2 == 0, "the two-stage schedule is written for an even number of k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
-    static_assert(WAVES * EPI_BYTES <= NSTAGE * STAGE_BYTES, "epilogue staging must fit");
+    static_assert(WAVES * EPI_BYTES + BN * 4 <= NSTAGE * STAGE_BYTES, "epilogue staging (and the bias strip) must fit");
     static_assert((NSTAGE - 2) * LPT <= 63, "vmcnt range");
     // loads of this iteration already issued when the tile barrier (before the last k-step) is reached
     constexpr int LOADS_BEFORE_BARRIER = ((KS - 1) * NM * LPT) / TOT;
@@ -264,20 +287,79 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     const int64_t a_chunk = ATile::chunk_step(p.lda), b_chunk = BTile::chunk_step(p.ldb);
     const int64_t a_ktile = ATile::ktile_step(p.lda), b_ktile = BTile::ktile_step(p.ldb);
     const int64_t kt0 = (int64_t)split * p.nk;   // first K-tile of this split
-    const Elem *a_src = static_cast<const Elem *>(p.A) + batch * p.sA + (AK ? m0 * p.lda : m0) + kt0 * a_ktile +
-                        ATile::lane_src(wave, lane, p.lda);
-    const Elem *b_src = static_cast<const Elem *>(p.B) + batch * p.sB + (BKM ? n0 * p.ldb : n0) + kt0 * b_ktile +
-                        BTile::lane_src(wave, lane, p.ldb);
+    const Elem *a_src, *b_src;
+    // MAPPED: distance from a wavefront's first chunk to its chunk idx (wave-uniform: a chunk's rows
+    // lie in one shard), and the position of the K walk inside the current shard / block
+    int64_t a_coff[ATile::CPW], b_coff[BTile::CPW];
+    int a_c1 = 0, a_c2 = 0, b_c1 = 0, b_c2 = 0;
+    if constexpr (!MAPPED) {
+        a_src = static_cast<const Elem *>(p.A) + batch * p.sA + (AK ? m0 * p.lda : m0) + kt0 * a_ktile +
+                ATile::lane_src(wave, lane, p.lda);
+        b_src = static_cast<const Elem *>(p.B) + batch * p.sB + (BKM ? n0 * p.ldb : n0) + kt0 * b_ktile +
+                BTile::lane_src(wave, lane, p.ldb);
+    } else {
+        constexpr int EPS = 16 / E::ELT;   // elements per 16-byte slot
+        {
+            const int first = wave * ATile::RPC + lane / ATile::SPR;   // tile row (K-major) or k-row (MN-major)
+            if constexpr (AK) {
+                const int c = (lane % ATile::SPR) ^ KMajorTile<E, BM, BKB>::swz(first);
+                a_src = static_cast<const Elem *>(p.A) + axis_offset(p.maps.a_mn, m0 + first) + c * EPS;
+                const int64_t base = axis_offset(p.maps.a_mn, m0 + wave * ATile::RPC);
+#pragma unroll
+                for (int idx = 0; idx < ATile::CPW; ++idx)
+                    a_coff[idx] = axis_offset(p.maps.a_mn, m0 + wave * ATile::RPC + idx * ATile::CHUNK_ROWS) - base;
+            } else {
+                const int slot = (lane % ATile::SPR) ^ E::mn_swz(first);
+                a_src = static_cast<const Elem *>(p.A) + axis_offset(p.maps.a_mn, m0 + slot * EPS) + first * p.maps.a_k.u;
+#pragma unroll
+                for (int idx = 0; idx < ATile::CPW; ++idx) a_coff[idx] = (int64_t)idx * ATile::CHUNK_ROWS * p.maps.a_k.u;
+            }
+        }
+        {
+            const int first = wave * BTile::RPC + lane / BTile::SPR;
+            if constexpr (BKM) {
+                const int c = (lane % BTile::SPR) ^ KMajorTile<E, BN, BKB>::swz(first);
+                b_src = static_cast<const Elem *>(p.B) + axis_offset(p.maps.b_mn, n0 + first) + c * EPS;
+                const int64_t base = axis_offset(p.maps.b_mn, n0 + wave * BTile::RPC);
+#pragma unroll
+                for (int idx = 0; idx < BTile::CPW; ++idx)
+                    b_coff[idx] = axis_offset(p.maps.b_mn, n0 + wave * BTile::RPC + idx * BTile::CHUNK_ROWS) - base;
+            } else {
+                const int slot = (lane % BTile::SPR) ^ E::mn_swz(first);
+                b_src = static_cast<const Elem *>(p.B) + axis_offset(p.maps.b_mn, n0 + slot * EPS) + first * p.maps.b_k.u;
+#pragma unroll
+                for (int idx = 0; idx < BTile::CPW; ++idx) b_coff[idx] = (int64_t)idx * BTile::CHUNK_ROWS * p.maps.b_k.u;
+            }
+        }
+    }
 
     // async load number idx (compile-time) of the tile the source pointers stand on
     auto issue_load = [&](int idx, int stage) {
         const unsigned a_lds = lds0 + stage * STAGE_BYTES + wave * 1024;
-        if (idx < ATile::CPW) async_load16(a_src + idx * a_chunk, a_lds + idx * (WAVES * 1024));
-        else async_load16(b_src + (idx - ATile::CPW) * b_chunk, a_lds + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
+        if constexpr (!MAPPED) {
+            if (idx < ATile::CPW) async_load16(a_src + idx * a_chunk, a_lds + idx * (WAVES * 1024));
+            else async_load16(b_src + (idx - ATile::CPW) * b_chunk, a_lds + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
+        } else {
+            if (idx < ATile::CPW) async_load16(a_src + a_coff[idx], a_lds + idx * (WAVES * 1024));
+            else async_load16(b_src + b_coff[idx - ATile::CPW], a_lds + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
+        }
     };
     auto next_tile = [&]() {
-        a_src += a_ktile;
-        b_src += b_ktile;
+        if constexpr (!MAPPED) {
+            a_src += a_ktile;
+            b_src += b_ktile;
+        } else {
+            constexpr int KPT = BKB / E::ELT;   // contraction indices per K-tile
+            int64_t da = p.ka.step, db = p.kb.step;
+            a_c1 += KPT; a_c2 += KPT;
+            if (a_c1 == p.ka.P1) { a_c1 = 0; a_c2 = 0; da += p.ka.jump1; }
+            else if (a_c2 == p.ka.P2) { a_c2 = 0; da += p.ka.jump2; }
+            b_c1 += KPT; b_c2 += KPT;
+            if (b_c1 == p.kb.P1) { b_c1 = 0; b_c2 = 0; db += p.kb.jump1; }
+            else if (b_c2 == p.kb.P2) { b_c2 = 0; db += p.kb.jump2; }
+            a_src += da;
+            b_src += db;
+        }
     };
 
     // ---- per-lane fragment addresses (relative to the stage base) -------------------------------------
@@ -459,9 +541,21 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // ---- epilogue: 32 rows at a time through a wave-private LDS strip -----------------------------------
     __syncthreads();   // all fragment reads of the stage buffers are done
     char *epi = smem + wave * EPI_BYTES;
-    TOut *C = static_cast<TOut *>(p.C) + batch * p.sC + split * p.sSplit + (m0 + wm * WM) * p.ldc + n0 + wn * WN;
     constexpr int LPR = WN * ESZ / 16;   // lanes per output row
     constexpr int RPP = 64 / LPR;        // rows per pass
+    TOut *C;
+    const float *bias_lds = nullptr;     // MAPPED with a bias: the bias of this wavefront's first column
+    if constexpr (!MAPPED) {
+        C = static_cast<TOut *>(p.C) + batch * p.sC + split * p.sSplit + (m0 + wm * WM) * p.ldc + n0 + wn * WN;
+    } else {
+        C = static_cast<TOut *>(p.C) + axis_offset(p.maps.c_n, n0 + wn * WN + (lane % LPR) * (16 / ESZ));
+        if (p.maps.bias) {
+            float *strip = reinterpret_cast<float *>(smem + WAVES * EPI_BYTES);
+            for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias[axis_offset(p.maps.bias_n, n0 + x)];
+            __syncthreads();
+            bias_lds = strip + wn * WN + 4 * (lane >> 5);
+        }
+    }
     const float alpha = p.alpha;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -471,8 +565,14 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             for (int g = 0; g < 4; ++g) {
                 // registers 4g..4g+3 of lane: row lane%32, columns j*32 + 8g + 4*(lane/32) + 0..3
                 char *dst = epi + (lane & 31) * EPI_STRIDE + (j * 32 + 8 * g + 4 * (lane >> 5)) * ESZ;
-                const float v0 = acc[i][j][4 * g] * alpha, v1 = acc[i][j][4 * g + 1] * alpha;
-                const float v2 = acc[i][j][4 * g + 2] * alpha, v3 = acc[i][j][4 * g + 3] * alpha;
+                float v0 = acc[i][j][4 * g] * alpha, v1 = acc[i][j][4 * g + 1] * alpha;
+                float v2 = acc[i][j][4 * g + 2] * alpha, v3 = acc[i][j][4 * g + 3] * alpha;
+                if constexpr (MAPPED) {
+                    if (bias_lds) {
+                        const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
+                        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+                    }
+                }
                 if (ESZ == 4) {
                     f32x4 v = {v0, v1, v2, v3};
                     *reinterpret_cast<f32x4 *>(dst) = v;
@@ -484,11 +584,15 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 }
             }
         }
+        int64_t strip = 0;   // MAPPED: where this 32-row strip (inside one shard) starts
+        if constexpr (MAPPED) strip = axis_offset(p.maps.c_m, m0 + wm * WM + i * 32);
 #pragma unroll
         for (int pass = 0; pass < 32 / RPP; ++pass) {
             const int row = pass * RPP + lane / LPR;
             const i32x4 v = *reinterpret_cast<const i32x4 *>(epi + row * EPI_STRIDE + (lane % LPR) * 16);
-            char *gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * p.ldc) + (lane % LPR) * 16;
+            char *gp;
+            if constexpr (!MAPPED) gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * p.ldc) + (lane % LPR) * 16;
+            else gp = reinterpret_cast<char *>(C + strip + (int64_t)row * p.maps.c_m.u);
             *reinterpret_cast<i32x4 *>(gp) = v;
         }
     }
@@ -496,14 +600,14 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
 
 // Launch one configuration.  splits > 1: every split writes its own fp32 partial result
 // [batch][split][Mo][No] to `out` (then out_ld = No); splits == 1: `out` is the final C.
-template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut>
+template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut, bool MAPPED = false>
 int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t out_batch_stride, int64_t out_split_stride,
                float alpha)
 {
     using ATile = typename std::conditional<AK, KMajorTile<E, BM, BKB>, MNMajorTile<E, BM, BKB>>::type;
     using BTile = typename std::conditional<BKM, KMajorTile<E, BN, BKB>, MNMajorTile<E, BN, BKB>>::type;
     constexpr int LDS = NSTAGE * (ATile::BYTES + BTile::BYTES);
-    auto kern = gemm_mfma_kernel<E, BM, BN, BKB, NSTAGE, AK, BKM, TOut>;
+    auto kern = gemm_mfma_kernel<E, BM, BN, BKB, NSTAGE, AK, BKM, TOut, MAPPED>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS) !=
@@ -524,6 +628,11 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
     p.splits = splits;
     p.sSplit = out_split_stride;
     p.alpha = alpha;
+    if (MAPPED) {
+        p.maps = *g.maps;
+        p.ka = make_kwalk(g.maps->a_k, BKB / E::ELT);
+        p.kb = make_kwalk(g.maps->b_k, BKB / E::ELT);
+    }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)(g.batch * splits), 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), LDS, g.stream, p);
     return launch_status();

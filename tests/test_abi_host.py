@@ -135,6 +135,24 @@ def test_bias_argument_errors(lib):
         assert f(ctypes.byref(d), c3.OPERAND_BIAS, None, FAKE, None) == c3.EINVAL
 
 
+def test_cube_linear_argument_errors(lib):
+    d = good()
+    f, dx, dw = lib.virtual_cube_linear_fwd, lib.virtual_cube_linear_bwd_dx, lib.virtual_cube_linear_bwd_dw
+    assert f(None, FAKE, FAKE, None, FAKE, None) == c3.EINVAL
+    assert f(ctypes.byref(d), None, FAKE, None, FAKE, None) == c3.EINVAL
+    assert f(ctypes.byref(d), FAKE, None, None, FAKE, None) == c3.EINVAL
+    assert f(ctypes.byref(d), FAKE, FAKE, None, None, None) == c3.EINVAL
+    assert f(ctypes.byref(d), FAKE, FAKE, ODD, FAKE, None) == c3.EINVAL        # misaligned bias
+    assert f(ctypes.byref(good(M=7)), FAKE, FAKE, None, FAKE, None) == c3.ESHAPE
+    assert f(ctypes.byref(good(in_dtype=11)), FAKE, FAKE, None, FAKE, None) == c3.EDTYPE
+    for g in (dx, dw):
+        assert g(None, FAKE, FAKE, FAKE, None) == c3.EINVAL
+        assert g(ctypes.byref(d), None, FAKE, FAKE, None) == c3.EINVAL
+        assert g(ctypes.byref(d), FAKE, ODD, FAKE, None) == c3.EINVAL
+        assert g(ctypes.byref(d), FAKE, FAKE, None, None) == c3.EINVAL
+        assert g(ctypes.byref(good(N=6)), FAKE, FAKE, FAKE, None) == c3.ESHAPE
+
+
 def test_workspace_query_and_strings(lib):
     assert c3.cube3d_workspace_bytes(good(M=7), c3.OP_FWD, False) == 0
     assert c3.cube3d_workspace_bytes(good(), 42, False) == 0
