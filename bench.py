@@ -239,6 +239,7 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
     n = q ** 3
     res = {}
     tot_flop, tot_ms = 0.0, 0.0
+    cube_flop, cube_ms = 0.0, 0.0
     for name, K, N, ax in CONFIG3:
         in_axis = c3.AXIS_Y if ax == "y" else c3.AXIS_Z
         out_axis = c3.AXIS_Z if ax == "y" else c3.AXIS_Y
@@ -313,11 +314,33 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
             ms = timed(fn, 10)
             r[k] = {"avg_us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                     "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
+        # the same three passes as ONE product each over the whole cube, shards read and written in
+        # place (no gathered copies, no partial products): flop as above, bytes = operands + result once
+        fused_ms = {}
+        for k, fn in (("cube_fwd_bias", lambda: c3.virtual_cube_linear_fwd(d, xs, ws, b_diag, ysh)),
+                      ("cube_bwd_dx", lambda: c3.virtual_cube_linear_bwd_dx(d, gs, ws, dxsh)),
+                      ("cube_bwd_dw", lambda: c3.virtual_cube_linear_bwd_dw(d, xs, gs, dwsh))):
+            fn()
+            ms = timed(fn, 10)
+            fused_ms[k] = ms
+            r[k] = {"avg_us": round(ms * 1e3, 1), "tflops": round(flop / (ms * 1e-3) / 1e12, 1)}
+        cube_flop += 3 * flop
+        cube_ms += sum(fused_ms.values())
+        # time of the same work through explicit collectives: gathers + batched product + reduce-scatter
+        r["speedup_vs_collective_path"] = {
+            "fwd": round((r["gather_x"]["avg_us"] + r["gather_w"]["avg_us"] + r["fwd"]["avg_us"] +
+                          r["reduce_scatter_y_bias"]["avg_us"]) / r["cube_fwd_bias"]["avg_us"], 2),
+            "bwd_dx": round((r["gather_dy"]["avg_us"] + r["gather_w"]["avg_us"] + r["bwd_dx"]["avg_us"] +
+                             r["reduce_scatter_dx"]["avg_us"]) / r["cube_bwd_dx"]["avg_us"], 2),
+            "bwd_dw": round((r["gather_x"]["avg_us"] + r["gather_dy"]["avg_us"] + r["bwd_dw"]["avg_us"] +
+                             r["reduce_scatter_dw"]["avg_us"]) / r["cube_bwd_dw"]["avg_us"], 2)}
         res[name] = r
         del xs, ws, gs, xb, wb, gb, P, ysh, Qv, Rv, buf, dxsh, dwsh, b_diag, b_blk, db
         torch.cuda.empty_cache()
     res["products_tflops"] = round(tot_flop / (tot_ms * 1e-3) / 1e12, 1)
     res["frac_of_bf16_peak"] = round(res["products_tflops"] / PEAK_TFLOPS["bf16"], 4)
+    res["cube_products_tflops"] = round(cube_flop / (cube_ms * 1e-3) / 1e12, 1)
+    res["cube_frac_of_bf16_peak"] = round(res["cube_products_tflops"] / PEAK_TFLOPS["bf16"], 4)
     return res
 
 
