@@ -390,15 +390,18 @@ __global__ __launch_bounds__(256) void cube_bias_bwd_rows_kernel(CubeGeom g, int
     }
 }
 
-// Stage 2: one block per (processor r, chunk of 64 of its Ns columns).  Processors off the diagonal
-// get zeros.  On the diagonal processor (i, a, a), lane = column; the terms t = (i'*q + b')*NRG + group
-// over every processor (i', a, b') of the output block's column of the cube are split into four
-// contiguous runs, one per wavefront, added in ascending order, and the four sums are added in
-// wavefront order: Algorithm 8's reduce along x plus the reduce along the output direction.
-__global__ __launch_bounds__(256) void cube_bias_bwd_finish_kernel(CubeGeom g, int NRG, float scale,
-                                                                   const float *__restrict__ part, float *__restrict__ db)
+// Stage 2: one block of sixteen wavefronts per (processor r, chunk of 64 of its Ns columns).
+// Processors off the diagonal get zeros.  On the diagonal processor (i, a, a), lane = column; the
+// terms t = (i'*q + b')*NRG + group over every processor (i', a, b') of the output block's column
+// of the cube are split into sixteen contiguous runs, one per wavefront, added in ascending order,
+// and the sixteen sums are added in wavefront order: Algorithm 8's reduce along x plus the reduce
+// along the output direction.
+constexpr int FIN_WAVES = 16;
+__global__ __launch_bounds__(64 * FIN_WAVES) void cube_bias_bwd_finish_kernel(CubeGeom g, int NRG, float scale,
+                                                                              const float *__restrict__ part,
+                                                                              float *__restrict__ db)
 {
-    __shared__ float lds[4][64];
+    __shared__ float lds[FIN_WAVES][64];
     constexpr int U = 8;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int r = blockIdx.x;
@@ -410,8 +413,8 @@ __global__ __launch_bounds__(256) void cube_bias_bwd_finish_kernel(CubeGeom g, i
         return;
     }
     const int a = j;
-    const int total = g.q * g.q * NRG, per = (total + 3) / 4;
-    const int t_lo = wave * per, t_hi = t_lo + per < total ? t_lo + per : total;
+    const int total = g.q * g.q * NRG, per = (total + FIN_WAVES - 1) / FIN_WAVES;
+    const int t_lo = wave * per < total ? wave * per : total, t_hi = t_lo + per < total ? t_lo + per : total;
     float acc = 0.f;
     for (int t0 = t_lo; t0 < t_hi; t0 += U) {
         float v[U];
@@ -430,8 +433,12 @@ __global__ __launch_bounds__(256) void cube_bias_bwd_finish_kernel(CubeGeom g, i
     }
     lds[wave][lane] = acc;
     __syncthreads();
-    if (wave == 0 && live)
-        db[(int64_t)r * g.Ns + c] = (((lds[0][lane] + lds[1][lane]) + lds[2][lane]) + lds[3][lane]) * scale;
+    if (wave == 0 && live) {
+        float sum = lds[0][lane];
+#pragma unroll
+        for (int w = 1; w < FIN_WAVES; ++w) sum += lds[w][lane];
+        db[(int64_t)r * g.Ns + c] = sum * scale;
+    }
 }
 
 template <typename T>
@@ -494,7 +501,7 @@ int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *d
     default: launch_bias_bwd_rows<unsigned char>(g, RG, NRG, dy_shards, part, stream); break;
     }
     dim3 grid2((unsigned)(g.q * g.q * g.q), (unsigned)((g.Ns + 63) / 64), 1);
-    hipLaunchKernelGGL(cube_bias_bwd_finish_kernel, grid2, dim3(256), 0, stream, g, NRG,
+    hipLaunchKernelGGL(cube_bias_bwd_finish_kernel, grid2, dim3(64 * FIN_WAVES), 0, stream, g, NRG,
                        dy_dtype == CUBE3D_FP8_E4M3 ? scale_dy : 1.f, part, dbias_diag);
     return launch_status();
 }
