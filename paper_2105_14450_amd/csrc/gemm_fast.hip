@@ -46,19 +46,23 @@ Plan make_plan(const GemmArgs &g)
         if (!map_ok(m.a_mn, g.Mo, align, !g.a_kmajor, 16) || !map_ok(m.b_mn, g.No, align, !g.b_kmajor, 16)) return p;
         if (!map_ok(m.c_m, g.Mo, oalign, false, 32) || !map_ok(m.c_n, g.No, oalign, true, oalign)) return p;
         if (m.bias && !map_ok(m.bias_n, g.No, 1, true, 4)) return p;
-        if (g.Kc % (fp8 ? 2 * kpt : kpt) || g.Kc < (fp8 ? 2 * kpt : kpt)) return p;   // fp8 K-tiles go in pairs
+        if (g.Kc % (4 * kpt)) return p;          // the K loop takes the four LDS stages per pass
+        // the kernel addresses an operand as buffer start + 32-bit byte offset
+        if ((axis_offset(m.a_mn, g.Mo - 1) + axis_offset(m.a_k, g.Kc - 1) + 1) * es >= (1ll << 32)) return p;
+        if ((axis_offset(m.b_mn, g.No - 1) + axis_offset(m.b_k, g.Kc - 1) + 1) * es >= (1ll << 32)) return p;
         const bool f256 = g.Mo % 256 == 0 && g.No % 256 == 0, f128 = !fp8 && g.Mo % 128 == 0 && g.No % 128 == 0;
         if (!f256 && !f128) return p;
         p.tile = (f256 && ((g.Mo / 256) * (g.No / 256) >= (3 * NUM_CU) / 4 || !f128)) ? 256 : 128;
         return p;
     }
     if (g.lda % align || g.ldb % align || g.strideA % align || g.strideB % align) return p;
+    // a tile's rows are addressed as tile start + 32-bit byte offset
+    if (g.lda * es * 256 >= (1ll << 32) || g.ldb * es * 256 >= (1ll << 32)) return p;
     if (g.ldc % 8 || g.strideC % 8) return p;
     if (g.batch > 16384) return p;
     if (g.out_dtype != CUBE3D_F32 && g.out_dtype != CUBE3D_BF16) return p;
     const int64_t ktile = 64 / es;              // K elements per 64-byte K-tile
-    // fp8: one MFMA k-step per K-tile, tiles are processed in pairs
-    if (g.Kc % (fp8 ? 2 * ktile : ktile) || g.Kc < (fp8 ? 2 * ktile : ktile)) return p;
+    if (g.Kc % (4 * ktile)) return p;           // the K loop takes the four LDS stages per pass
     const int64_t nk = g.Kc / ktile;
     const bool fits256 = g.Mo % 256 == 0 && g.No % 256 == 0;
     const bool fits128 = !fp8 && g.Mo % 128 == 0 && g.No % 128 == 0;
@@ -70,7 +74,7 @@ Plan make_plan(const GemmArgs &g)
     // splits * Mo * No * 4 bytes of HBM traffic each way, so keep them few and small.
     const int64_t tiles = (g.Mo / p.tile) * (g.No / p.tile) * g.batch;
     int splits = 1;
-    while (tiles * splits * 2 <= NUM_CU / 2 && splits < 16 && nk % (splits * 4) == 0 && nk / (splits * 2) >= 16 &&
+    while (tiles * splits * 2 <= NUM_CU / 2 && splits < 16 && nk % (splits * 8) == 0 && nk / (splits * 2) >= 16 &&
            (int64_t)splits * 2 * g.Mo * g.No * g.batch * 4 <= (32ll << 20))
         splits *= 2;
     if ((int64_t)g.batch * splits > 65535) splits = 1;
@@ -105,14 +109,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
-// K-tile depth and pipeline depth per operand layout (measured on config-4 shapes): with both
-// operands K-major a 128-byte K-tile (whole cache lines per row) and two stages is ~3 % faster;
-// the layouts with a transposed operand prefer 64-byte K-tiles four stages deep.
+// 64-byte K-tiles, four LDS stages for every operand layout (deeper K-tiles leave room for two
+// stages only, whose loads then come in bursts that hold up the MFMA stream).
 template <typename E, int T, typename TOut>
 int launch_for_layout(const GemmArgs &g, int splits, void *out, int64_t ld, int64_t bs, int64_t ss)
 {
-    if (g.a_kmajor && g.b_kmajor && T == 256 && (g.Kc * E::ELT / splits) % 128 == 0)
-        return launch_cfg<E, T, T, 128, 2, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
     return launch_layout<E, T, T, 64, 4, TOut>(g, splits, out, ld, bs, ss, g.alpha);
 }
 

@@ -19,6 +19,17 @@
 // The MFMA is issued with the operands exchanged (B fragment first), so a lane's accumulator
 // registers hold 4 consecutive output columns of one output row and the epilogue can move
 // packed rows through LDS into 16-byte coalesced stores.
+//
+// Issue schedule.  With one wavefront per SIMD the matrix pipe stays full only if the wavefront
+// is back at the next MFMA when the previous one retires (32 cycles): everything else has to fit
+// into those gaps, a few instructions per gap.  Measured on gfx950: an LDS read with an
+// immediate offset or a direct-to-LDS load addressed as scalar base + 32-bit lane offset costs
+// no MFMA time when it sits alone in a gap; address arithmetic on the vector ALU, loads with
+// 64-bit lane addresses, bursts of scalar instructions and, most of all, branches do.  So the
+// K loop is unrolled over the NSTAGE stages (every LDS address is a lane-constant register plus
+// an immediate, every M0 value a scalar add of a constant), the global addresses are one scalar
+// pointer per operand advanced once per K-tile plus lane-constant offsets, and the reads and
+// loads of a k-step are dealt out one per gap.
 #pragma once
 #include <type_traits>
 
@@ -28,7 +39,6 @@ namespace cube3d {
 namespace mfk {
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int WAVES = 4;
@@ -53,67 +63,65 @@ template <int N> __device__ __forceinline__ void tile_barrier()
     asm volatile("" ::: "memory");
 }
 
-// Direct-to-LDS 16-byte load: lane s of the wavefront writes LDS bytes [lds_base + 16 s, +16).
+// Direct-to-LDS 16-byte load: lane s of the wavefront writes LDS bytes [lds_base + 16 s, +16)
+// with the 16 bytes at base + offset (scalar 64-bit base, 32-bit unsigned lane offset).
 // Issued as inline assembly so that its completion is tracked by the explicit
 // s_waitcnt vmcnt(..) + barrier of the pipeline and by nothing else (the compiler would
 // otherwise drain every outstanding load before each LDS read).
-__device__ __forceinline__ void async_load16(const void *gptr, unsigned lds_base)
+__device__ __forceinline__ void async_load16(const char *base, unsigned offset, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_base) : "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(offset), "s"(base), "s"(lds_base) : "m0");
+}
+
+// -1 if the two wavefront-uniform values are equal, else 0; opaque to the compiler, which would
+// otherwise turn arithmetic on the result back into a branch.
+__device__ __forceinline__ int eq_mask(int a, int b)
+{
+    int m;
+    asm volatile("s_cmp_eq_u32 %1, %2\n\ts_cselect_b32 %0, -1, 0" : "=s"(m) : "s"(a), "s"(b) : "scc");
+    return m;
 }
 
 // ---- element traits --------------------------------------------------------------------------------
+// A fragment (one operand of one MFMA: 32 rows or columns x one k-step) is FI 32-bit registers
+// per lane, read from LDS in pieces: PK 16-byte reads when the operand is K-major, PT
+// transposing 8-byte reads (TR_ROWS k-rows apart) when it is MN-major.
 struct Bf16 {
     typedef unsigned short Elem;
-    typedef bf16x8 Frag;                        // 8 bf16 = 16 bytes per lane
+    typedef i32x4 FragI;                        // 8 bf16 = 16 bytes per lane
     static constexpr int ELT = 2;
     static constexpr int KSTEP = 16;            // k per MFMA
     static constexpr int TR_ROWS = 4;           // k-rows covered by one transposing read
+    static constexpr int FI = 4, PK = 1, PT = 2;
     __device__ static __forceinline__ int mn_swz(int k) { return 4 * (k & 3); }
-    __device__ static __forceinline__ f32x16 mfma(Frag first, Frag second, f32x16 c)
+    __device__ static __forceinline__ f32x16 mfma(FragI first, FragI second, f32x16 c)
     {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(first, second, c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second),
+                                                       c, 0, 0, 0);
     }
-    // K-major fragment: 16 bytes at `ad`
-    __device__ static __forceinline__ Frag read_k(unsigned ad0, unsigned) { return *(CUBE3D_LDS(Frag))(uintptr_t)ad0; }
-    // MN-major fragment: two transposing reads, k-rows +0..3 and +4..7
-    __device__ static __forceinline__ Frag read_tr(unsigned ad, int row_bytes)
+    __device__ static __forceinline__ i32x2 read_tr(unsigned ad)
     {
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(uintptr_t)ad);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4 *)(uintptr_t)(ad + 4 * row_bytes));
-        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(Frag, v);
+        return __builtin_bit_cast(
+            i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(uintptr_t)ad));
     }
 };
 
 struct Fp8 {
     typedef unsigned char Elem;
-    typedef i32x8 Frag;                         // 32 fp8 = 32 bytes per lane
+    typedef i32x8 FragI;                        // 32 fp8 = 32 bytes per lane
     static constexpr int ELT = 1;
     static constexpr int KSTEP = 64;
     static constexpr int TR_ROWS = 8;
+    static constexpr int FI = 8, PK = 2, PT = 4;
     __device__ static __forceinline__ int mn_swz(int k) { return 2 * (k & 7); }
-    __device__ static __forceinline__ f32x16 mfma(Frag first, Frag second, f32x16 c)
+    __device__ static __forceinline__ f32x16 mfma(FragI first, FragI second, f32x16 c)
     {
         // both operands e4m3 (format code 0), block scales 2^0
         return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(first, second, c, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
     }
-    __device__ static __forceinline__ Frag read_k(unsigned ad0, unsigned ad1)
+    __device__ static __forceinline__ i32x2 read_tr(unsigned ad)
     {
-        const i32x4 lo = *(CUBE3D_LDS(i32x4))(uintptr_t)ad0;
-        const i32x4 hi = *(CUBE3D_LDS(i32x4))(uintptr_t)ad1;
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    }
-    __device__ static __forceinline__ Frag read_tr(unsigned ad, int row_bytes)
-    {
-        i32x2 r[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            r[j] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                (__attribute__((address_space(3))) i32x2 *)(uintptr_t)(ad + 8 * j * row_bytes));
-        Frag f = {r[0][0], r[0][1], r[1][0], r[1][1], r[2][0], r[2][1], r[3][0], r[3][1]};
-        return f;
+        return __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) i32x2 *)(uintptr_t)ad);
     }
 };
 
@@ -177,9 +185,13 @@ template <typename E, int COLS, int BKB> struct MNMajorTile {
     }
 };
 
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
 {
-    return (unsigned)f32_to_bf16_bits(lo) | ((unsigned)f32_to_bf16_bits(hi) << 16);
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 
 // Advance of a map-addressed operand from one K-tile to the next (all values in elements): the
@@ -219,41 +231,37 @@ struct Params {
 
 // TOut: float or unsigned short (bf16 bits).  MAPPED: operands, output and the optional bias are
 // addressed through p.maps (a cube of shards read in place) instead of leading dimensions.
+// The number of K-tiles per workgroup (p.nk) must be a positive multiple of NSTAGE.
 template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut, bool MAPPED = false>
 __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma_kernel(const Params p)
 {
     typedef typename E::Elem Elem;
-    typedef typename E::Frag Frag;
+    typedef typename E::FragI FragI;
     using ATile = typename std::conditional<AK, KMajorTile<E, BM, BKB>, MNMajorTile<E, BM, BKB>>::type;
     using BTile = typename std::conditional<BKM, KMajorTile<E, BN, BKB>, MNMajorTile<E, BN, BKB>>::type;
     constexpr int A_BYTES = ATile::BYTES, B_BYTES = BTile::BYTES, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int KS = BKB / (E::KSTEP * E::ELT);      // k-steps (MFMAs deep) per K-tile
-    constexpr int NM = TM * TN;                        // MFMAs per k-step
-    constexpr int NR = TM + TN;                        // fragments per k-step
+    constexpr int NM = TM * TN;                        // MFMAs per k-step = gaps per k-step
     constexpr int LPT = ATile::CPW + BTile::CPW;       // async loads per K-tile per wavefront
-    constexpr int TOT = KS * NM;                       // MFMAs per K-tile
-    constexpr int UNROLL = (KS % 2) ? 2 : 1;           // K-tiles per loop body (fragment buffers alternate per k-step)
+    constexpr int LPK = LPT / KS;                      // ... per k-step
+    constexpr int PA = AK ? E::PK : E::PT, PB = BKM ? E::PK : E::PT;   // LDS reads per fragment
+    constexpr int NRD = TM * PA + TN * PB;             // LDS reads per k-step
+    constexpr int RG = NM > 4 ? NM - 2 : NM;           // gaps of a k-step that take the reads of the next one
+    constexpr int NBA = AK ? KS * E::PK : TM;          // lane-constant LDS address registers per operand
+    constexpr int NBB = BKM ? KS * E::PK : TN;
+    constexpr int PRE = NSTAGE - 1;                    // tiles in flight after the prologue
     constexpr int ESZ = sizeof(TOut);
     constexpr int EPI_STRIDE = WN * ESZ + 16;
     constexpr int EPI_BYTES = 32 * EPI_STRIDE;
-    constexpr int FS = (E::KSTEP * E::ELT / 2) / 16;   // 16-byte reads per K-major fragment
     static_assert(KS >= 1 && BKB % (E::KSTEP * E::ELT) == 0, "K-tile must hold whole k-steps");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wavefront tile is made of 32x32 MFMA tiles");
-    // NSTAGE >= 3: the loads of tile kt+NSTAGE-1 are spread over the whole of iteration kt.
-    // NSTAGE == 2: the loads of tile kt+2 go into the stage of tile kt as soon as the barrier
-    // before its last k-step has shown that nobody reads it any more (all behind that k-step's MFMAs).
-    constexpr bool TWO_STAGE = NSTAGE == 2;
-    constexpr int PRE = TWO_STAGE ? 2 : NSTAGE - 1;    // tiles in flight after the prologue
-    static_assert(NSTAGE >= 2, "at least double buffering");
-    static_assert(!TWO_STAGE || KS % 2 == 0, "the two-stage schedule is written for an even number of k-steps");
+    static_assert(NSTAGE >= 3 && (NSTAGE * KS) % 2 == 0, "the fragment buffers alternate per k-step and must line up per pass over the stages");
+    static_assert(LPT % KS == 0, "the loads of a K-tile are dealt out evenly over its k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(NSTAGE * STAGE_BYTES <= 2 * 65536, "an LDS address is one of two lane registers plus a 16-bit immediate");
     static_assert(WAVES * EPI_BYTES + BN * 4 <= NSTAGE * STAGE_BYTES, "epilogue staging (and the bias strip) must fit");
     static_assert((NSTAGE - 2) * LPT <= 63, "vmcnt range");
-    // loads of this iteration already issued when the tile barrier (before the last k-step) is reached
-    constexpr int LOADS_BEFORE_BARRIER = ((KS - 1) * NM * LPT) / TOT;
-    // loads that may still be in flight behind the steady-state barrier: those of the tiles after kt+1
-    constexpr int STEADY_VMCNT = (NSTAGE == 2) ? 0 : (NSTAGE - 3) * LPT + LOADS_BEFORE_BARRIER;
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
@@ -283,128 +291,172 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     const int batch = blockIdx.y / p.splits;
     const int split = blockIdx.y - batch * p.splits;
 
-    // ---- global source pointers of this lane's async loads -------------------------------------------
-    const int64_t a_chunk = ATile::chunk_step(p.lda), b_chunk = BTile::chunk_step(p.ldb);
-    const int64_t a_ktile = ATile::ktile_step(p.lda), b_ktile = BTile::ktile_step(p.ldb);
-    const int64_t kt0 = (int64_t)split * p.nk;   // first K-tile of this split
-    const Elem *a_src, *b_src;
-    // MAPPED: distance from a wavefront's first chunk to its chunk idx (wave-uniform: a chunk's rows
-    // lie in one shard), and the position of the K walk inside the current shard / block
-    int64_t a_coff[ATile::CPW], b_coff[BTile::CPW];
-    int a_c1 = 0, a_c2 = 0, b_c1 = 0, b_c2 = 0;
+    // ---- global sources of this lane's async loads: one scalar pointer per operand, standing on the
+    //      K-tile that is loaded next, plus one 32-bit byte offset per load that never changes
+    const char *a_base, *b_base;
+    unsigned a_voff[ATile::CPW], b_voff[BTile::CPW];
+    int64_t a_step = 0, b_step = 0;              // bytes from one K-tile to the next (plain operands)
+    int a_c1 = 0, a_c2 = 0, b_c1 = 0, b_c2 = 0;  // MAPPED: position of the K walk inside the current block / shard
     if constexpr (!MAPPED) {
-        a_src = static_cast<const Elem *>(p.A) + batch * p.sA + (AK ? m0 * p.lda : m0) + kt0 * a_ktile +
-                ATile::lane_src(wave, lane, p.lda);
-        b_src = static_cast<const Elem *>(p.B) + batch * p.sB + (BKM ? n0 * p.ldb : n0) + kt0 * b_ktile +
-                BTile::lane_src(wave, lane, p.ldb);
+        const int64_t kt0 = (int64_t)split * p.nk;   // first K-tile of this split
+        a_step = ATile::ktile_step(p.lda) * E::ELT;
+        b_step = BTile::ktile_step(p.ldb) * E::ELT;
+        a_base = static_cast<const char *>(p.A) + (batch * p.sA + (AK ? m0 * p.lda : m0)) * E::ELT + kt0 * a_step;
+        b_base = static_cast<const char *>(p.B) + (batch * p.sB + (BKM ? n0 * p.ldb : n0)) * E::ELT + kt0 * b_step;
+#pragma unroll
+        for (int idx = 0; idx < ATile::CPW; ++idx)
+            a_voff[idx] = (unsigned)((ATile::lane_src(wave, lane, p.lda) + idx * ATile::chunk_step(p.lda)) * E::ELT);
+#pragma unroll
+        for (int idx = 0; idx < BTile::CPW; ++idx)
+            b_voff[idx] = (unsigned)((BTile::lane_src(wave, lane, p.ldb) + idx * BTile::chunk_step(p.ldb)) * E::ELT);
     } else {
+        // offsets relative to the start of the operand's cube buffer (the launcher checks that the
+        // buffer is shorter than 4 GB); a chunk's rows lie in one shard
         constexpr int EPS = 16 / E::ELT;   // elements per 16-byte slot
+        a_base = static_cast<const char *>(p.A);
+        b_base = static_cast<const char *>(p.B);
         {
             const int first = wave * ATile::RPC + lane / ATile::SPR;   // tile row (K-major) or k-row (MN-major)
-            if constexpr (AK) {
-                const int c = (lane % ATile::SPR) ^ KMajorTile<E, BM, BKB>::swz(first);
-                a_src = static_cast<const Elem *>(p.A) + axis_offset(p.maps.a_mn, m0 + first) + c * EPS;
-                const int64_t base = axis_offset(p.maps.a_mn, m0 + wave * ATile::RPC);
 #pragma unroll
-                for (int idx = 0; idx < ATile::CPW; ++idx)
-                    a_coff[idx] = axis_offset(p.maps.a_mn, m0 + wave * ATile::RPC + idx * ATile::CHUNK_ROWS) - base;
-            } else {
-                const int slot = (lane % ATile::SPR) ^ E::mn_swz(first);
-                a_src = static_cast<const Elem *>(p.A) + axis_offset(p.maps.a_mn, m0 + slot * EPS) + first * p.maps.a_k.u;
-#pragma unroll
-                for (int idx = 0; idx < ATile::CPW; ++idx) a_coff[idx] = (int64_t)idx * ATile::CHUNK_ROWS * p.maps.a_k.u;
+            for (int idx = 0; idx < ATile::CPW; ++idx) {
+                int64_t off;
+                if constexpr (AK) {
+                    const int c = (lane % ATile::SPR) ^ KMajorTile<E, BM, BKB>::swz(first);
+                    off = axis_offset(p.maps.a_mn, m0 + first + idx * ATile::CHUNK_ROWS) + c * EPS;
+                } else {
+                    const int slot = (lane % ATile::SPR) ^ E::mn_swz(first);
+                    off = axis_offset(p.maps.a_mn, m0 + slot * EPS) + (int64_t)(first + idx * ATile::CHUNK_ROWS) * p.maps.a_k.u;
+                }
+                a_voff[idx] = (unsigned)(off * E::ELT);
             }
         }
         {
             const int first = wave * BTile::RPC + lane / BTile::SPR;
-            if constexpr (BKM) {
-                const int c = (lane % BTile::SPR) ^ KMajorTile<E, BN, BKB>::swz(first);
-                b_src = static_cast<const Elem *>(p.B) + axis_offset(p.maps.b_mn, n0 + first) + c * EPS;
-                const int64_t base = axis_offset(p.maps.b_mn, n0 + wave * BTile::RPC);
 #pragma unroll
-                for (int idx = 0; idx < BTile::CPW; ++idx)
-                    b_coff[idx] = axis_offset(p.maps.b_mn, n0 + wave * BTile::RPC + idx * BTile::CHUNK_ROWS) - base;
-            } else {
-                const int slot = (lane % BTile::SPR) ^ E::mn_swz(first);
-                b_src = static_cast<const Elem *>(p.B) + axis_offset(p.maps.b_mn, n0 + slot * EPS) + first * p.maps.b_k.u;
-#pragma unroll
-                for (int idx = 0; idx < BTile::CPW; ++idx) b_coff[idx] = (int64_t)idx * BTile::CHUNK_ROWS * p.maps.b_k.u;
+            for (int idx = 0; idx < BTile::CPW; ++idx) {
+                int64_t off;
+                if constexpr (BKM) {
+                    const int c = (lane % BTile::SPR) ^ KMajorTile<E, BN, BKB>::swz(first);
+                    off = axis_offset(p.maps.b_mn, n0 + first + idx * BTile::CHUNK_ROWS) + c * EPS;
+                } else {
+                    const int slot = (lane % BTile::SPR) ^ E::mn_swz(first);
+                    off = axis_offset(p.maps.b_mn, n0 + slot * EPS) + (int64_t)(first + idx * BTile::CHUNK_ROWS) * p.maps.b_k.u;
+                }
+                b_voff[idx] = (unsigned)(off * E::ELT);
             }
         }
     }
 
-    // async load number idx (compile-time) of the tile the source pointers stand on
+    // async load number idx of the K-tile the scalar pointers stand on, into LDS stage `stage`
+    // (idx and stage are constants wherever this is called: the LDS address is wave base + constant)
+    unsigned wave_lds = lds0 + wave * 1024;
     auto issue_load = [&](int idx, int stage) {
-        const unsigned a_lds = lds0 + stage * STAGE_BYTES + wave * 1024;
-        if constexpr (!MAPPED) {
-            if (idx < ATile::CPW) async_load16(a_src + idx * a_chunk, a_lds + idx * (WAVES * 1024));
-            else async_load16(b_src + (idx - ATile::CPW) * b_chunk, a_lds + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
-        } else {
-            if (idx < ATile::CPW) async_load16(a_src + a_coff[idx], a_lds + idx * (WAVES * 1024));
-            else async_load16(b_src + b_coff[idx - ATile::CPW], a_lds + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
-        }
+        if (idx < ATile::CPW) async_load16(a_base, a_voff[idx], wave_lds + stage * STAGE_BYTES + idx * (WAVES * 1024));
+        else async_load16(b_base, b_voff[idx - ATile::CPW],
+                          wave_lds + stage * STAGE_BYTES + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
     };
-    auto next_tile = [&]() {
+    // Move an operand's scalar pointer to the next K-tile.  MAPPED: the walk along the contraction
+    // index steps through shards and blocks; the corrections are selected with masks, because a
+    // branch in the K loop holds up the MFMA stream far longer than a dozen scalar instructions.
+    auto advance = [&](const char *&base, int64_t plain_step, const KWalk &w, int &c1, int &c2) {
         if constexpr (!MAPPED) {
-            a_src += a_ktile;
-            b_src += b_ktile;
+            base += plain_step;
         } else {
             constexpr int KPT = BKB / E::ELT;   // contraction indices per K-tile
-            int64_t da = p.ka.step, db = p.kb.step;
-            a_c1 += KPT; a_c2 += KPT;
-            if (a_c1 == p.ka.P1) { a_c1 = 0; a_c2 = 0; da += p.ka.jump1; }
-            else if (a_c2 == p.ka.P2) { a_c2 = 0; da += p.ka.jump2; }
-            b_c1 += KPT; b_c2 += KPT;
-            if (b_c1 == p.kb.P1) { b_c1 = 0; b_c2 = 0; db += p.kb.jump1; }
-            else if (b_c2 == p.kb.P2) { b_c2 = 0; db += p.kb.jump2; }
-            a_src += da;
-            b_src += db;
+            c1 += KPT;
+            c2 += KPT;
+            const int64_t off_block = eq_mask(c1, w.P1);                 // all ones: the tile walked off a block
+            const int64_t off_shard = eq_mask(c2, w.P2) & ~off_block;    // ... off a shard inside the block
+            base += (w.step + (w.jump1 & off_block) + (w.jump2 & off_shard)) * E::ELT;
+            c1 &= (int)~off_block;
+            c2 &= (int)~(off_block | off_shard);
         }
     };
+    auto advance_a = [&]() { advance(a_base, a_step, p.ka, a_c1, a_c2); };
+    auto advance_b = [&]() { advance(b_base, b_step, p.kb, b_c1, b_c2); };
 
-    // ---- per-lane fragment addresses (relative to the stage base) -------------------------------------
-    unsigned a_addr[AK ? KS * FS : TM], b_addr[BKM ? KS * FS : TN];
-    if (AK) {
+    // ---- lane-constant LDS addresses of the fragment reads; every read adds an immediate -------------
+    // K-major operand: one register per 16-byte piece of a k-step; MN-major operand: one per 32-wide
+    // block of the wavefront's sub-tile.  Each exists twice, 64 KB apart, so that the immediate
+    // (stage, operand, block, k-step, piece) always fits the 16-bit offset field of the read.
+    // (fp8 fragments are twice as large: there the registers are needed for the fragments, and the
+    // reads of the upper stages form their address with one add instead.)
+    constexpr bool HI_REGS = E::FI <= 4;
+    unsigned a_lo[NBA], a_hi[NBA], b_lo[NBB], b_hi[NBB];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int f = 0; f < FS; ++f)
-                a_addr[ks * FS + f] =
-                    KMajorTile<E, BM, BKB>::slot_addr(wm * WM + (lane & 31), ks * 2 * FS + (lane >> 5) * FS + f);
-    } else {
-#pragma unroll
-        for (int t = 0; t < TM; ++t) a_addr[t] = MNMajorTile<E, BM, BKB>::tr_addr(lane, wm * TM + t);
+    for (int x = 0; x < NBA; ++x) {
+        if constexpr (AK)
+            a_lo[x] = lds0 + KMajorTile<E, BM, BKB>::slot_addr(wm * WM + (lane & 31),
+                                                               (x / E::PK) * 2 * E::PK + (lane >> 5) * E::PK + x % E::PK);
+        else a_lo[x] = lds0 + MNMajorTile<E, BM, BKB>::tr_addr(lane, wm * TM + x);
+        a_hi[x] = a_lo[x] + 65536;
+        if constexpr (HI_REGS) asm volatile("" : "+v"(a_hi[x]));   // keep it in a register of its own
     }
-    if (BKM) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int f = 0; f < FS; ++f)
-                b_addr[ks * FS + f] = A_BYTES + KMajorTile<E, BN, BKB>::slot_addr(wn * WN + (lane & 31),
-                                                                                 ks * 2 * FS + (lane >> 5) * FS + f);
-    } else {
-#pragma unroll
-        for (int t = 0; t < TN; ++t) b_addr[t] = A_BYTES + MNMajorTile<E, BN, BKB>::tr_addr(lane, wn * TN + t);
+    for (int x = 0; x < NBB; ++x) {
+        if constexpr (BKM)
+            b_lo[x] = lds0 + KMajorTile<E, BN, BKB>::slot_addr(wn * WN + (lane & 31),
+                                                               (x / E::PK) * 2 * E::PK + (lane >> 5) * E::PK + x % E::PK);
+        else b_lo[x] = lds0 + MNMajorTile<E, BN, BKB>::tr_addr(lane, wn * TN + x);
+        b_hi[x] = b_lo[x] + 65536;
+        if constexpr (HI_REGS) asm volatile("" : "+v"(b_hi[x]));
     }
 
-    // one fragment (32 rows or columns x one k-step) from the stage at stage_base
-    auto read_a = [&](unsigned stage_base, int ks, int t) -> Frag {
-        if (AK) {
-            const unsigned off = stage_base + t * KMajorTile<E, BM, BKB>::BLOCK_STEP;
-            return E::read_k(off + a_addr[ks * FS], off + a_addr[ks * FS + FS - 1]);
+    // A fragment is kept as the pieces it was read in (whole registers each, so that no read
+    // rewrites part of a live value) and put together where the MFMA takes it.
+    using APiece = typename std::conditional<AK, i32x4, i32x2>::type;
+    using BPiece = typename std::conditional<BKM, i32x4, i32x2>::type;
+    APiece fa[2][TM][PA];
+    BPiece fb[2][TN][PB];
+    // piece `pc` of the fragment of block t, k-step ks, in LDS stage `stage`, into fragment buffer `buf`
+    auto read_a = [&](int buf, int stage, int ks, int t, int pc) {
+        if constexpr (AK) {
+            const int c = stage * STAGE_BYTES + t * KMajorTile<E, BM, BKB>::BLOCK_STEP;
+            const int x = ks * E::PK + pc;
+            const unsigned ad = c < 65536 ? a_lo[x] + c : a_hi[x] + (c - 65536);
+            fa[buf][t][pc] = *(CUBE3D_LDS(i32x4))(uintptr_t)ad;
         } else {
             constexpr int RB = MNMajorTile<E, BM, BKB>::RB;
-            return E::read_tr(stage_base + a_addr[t] + ks * E::KSTEP * RB, RB);
+            const int c = stage * STAGE_BYTES + (ks * E::KSTEP + pc * E::TR_ROWS) * RB;
+            fa[buf][t][pc] = E::read_tr(c < 65536 ? a_lo[t] + c : a_hi[t] + (c - 65536));
         }
     };
-    auto read_b = [&](unsigned stage_base, int ks, int t) -> Frag {
-        if (BKM) {
-            const unsigned off = stage_base + t * KMajorTile<E, BN, BKB>::BLOCK_STEP;
-            return E::read_k(off + b_addr[ks * FS], off + b_addr[ks * FS + FS - 1]);
+    auto read_b = [&](int buf, int stage, int ks, int t, int pc) {
+        if constexpr (BKM) {
+            const int c = stage * STAGE_BYTES + A_BYTES + t * KMajorTile<E, BN, BKB>::BLOCK_STEP;
+            const int x = ks * E::PK + pc;
+            const unsigned ad = c < 65536 ? b_lo[x] + c : b_hi[x] + (c - 65536);
+            fb[buf][t][pc] = *(CUBE3D_LDS(i32x4))(uintptr_t)ad;
         } else {
             constexpr int RB = MNMajorTile<E, BN, BKB>::RB;
-            return E::read_tr(stage_base + b_addr[t] + ks * E::KSTEP * RB, RB);
+            const int c = stage * STAGE_BYTES + A_BYTES + (ks * E::KSTEP + pc * E::TR_ROWS) * RB;
+            fb[buf][t][pc] = E::read_tr(c < 65536 ? b_lo[t] + c : b_hi[t] + (c - 65536));
         }
+    };
+    auto frag_a = [&](int buf, int t) -> FragI {
+        FragI f;
+        constexpr int W = AK ? 4 : 2;
+#pragma unroll
+        for (int pc = 0; pc < PA; ++pc)
+#pragma unroll
+            for (int e = 0; e < W; ++e) f[pc * W + e] = fa[buf][t][pc][e];
+        return f;
+    };
+    auto frag_b = [&](int buf, int t) -> FragI {
+        FragI f;
+        constexpr int W = BKM ? 4 : 2;
+#pragma unroll
+        for (int pc = 0; pc < PB; ++pc)
+#pragma unroll
+            for (int e = 0; e < W; ++e) f[pc * W + e] = fb[buf][t][pc][e];
+        return f;
+    };
+    // LDS read number r of a k-step, in the order the MFMAs (block row i outer, block column j
+    // inner) first need the fragments: A0, B0 .. B(TN-1), A1 .. A(TM-1)
+    auto read_piece = [&](int r, int buf, int stage, int ks) {
+        if (r < PA) read_a(buf, stage, ks, 0, r);
+        else if (r < PA + TN * PB) read_b(buf, stage, ks, (r - PA) / PB, (r - PA) % PB);
+        else read_a(buf, stage, ks, 1 + (r - PA - TN * PB) / PA, (r - PA - TN * PB) % PA);
     };
 
     f32x16 acc[TM][TN];
@@ -415,127 +467,90 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // ---- pipeline prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed ------------------------------
-    const int nk = p.nk;
+    // ---- pipeline prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed, its first fragments read --------
 #pragma unroll
     for (int s = 0; s < PRE; ++s) {
-        if (s < nk) {
 #pragma unroll
-            for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
-            next_tile();
-        }
+        for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
+        advance_a();
+        advance_b();
     }
-    if (nk >= PRE) tile_barrier<(PRE - 1) * LPT>();
-    else tile_barrier<0>();
-
-    Frag fa[2][TM], fb[2][TN];
+    tile_barrier<(PRE - 1) * LPT>();
 #pragma unroll
-    for (int t = 0; t < TM; ++t) fa[0][t] = read_a(lds0, 0, t);
-#pragma unroll
-    for (int t = 0; t < TN; ++t) fb[0][t] = read_b(lds0, 0, t);
+    for (int r = 0; r < NRD; ++r) read_piece(r, 0, 0, 0);
 
     // ---- main loop ----------------------------------------------------------------------------------
-    // Each k-step issues its MFMAs in a fixed order with, spread between them, the fragment reads of
-    // the following k-step and this step's share of the async loads of tile kt+NSTAGE-1.  The order
-    // is pinned with scheduling barriers: with one wavefront per SIMD nothing else hides a latency,
-    // so reads must be in flight well before their first use.  The body is instantiated for the
-    // steady state, the drain and the last tile so that the hot loop carries no branches.
-    int stage = 0;
-    auto k_tile = [&](auto more_c, auto has_next_c, auto parity_c) {
+    // K-tile number kt lives in stage kt mod NSTAGE; one pass of the loop body takes NSTAGE tiles, so
+    // stage, fragment buffer and every address constant are fixed per copy of the tile body.  Per
+    // k-step: NM MFMAs; behind MFMA g come the LDS reads of the following k-step that fall into gap g
+    // (all of them inside the first RG gaps, so that they have landed when the tile barrier or the next
+    // k-step asks for them) and this k-step's share of the async loads of tile kt+NSTAGE-1.  The order
+    // is pinned with scheduling barriers.  ALLOW = loads that may stay in flight across the tile barrier.
+    auto k_tile = [&](auto stage_c, auto more_c, auto has_next_c, auto allow_c) {
+        constexpr int stage = decltype(stage_c)::value;
         constexpr bool more = decltype(more_c)::value;          // tile kt+PRE exists: load it
         constexpr bool has_next = decltype(has_next_c)::value;  // tile kt+1 exists
-        constexpr int parity = decltype(parity_c)::value;       // fragment buffer holding this tile's k-step 0
-        const unsigned stage_base = lds0 + stage * STAGE_BYTES;
-        int pre = TWO_STAGE ? stage : stage + NSTAGE - 1;   // stage the loads of this iteration go to
-        if (pre >= NSTAGE) pre -= NSTAGE;
-        int next = stage + 1;
-        if (next == NSTAGE) next = 0;
-        const unsigned next_base = lds0 + next * STAGE_BYTES;
+        constexpr int ALLOW = decltype(allow_c)::value;
+        constexpr int pre = (stage + NSTAGE - 1) % NSTAGE;      // stage the loads of this tile body go to
+        constexpr int next = (stage + 1) % NSTAGE;
+        constexpr int parity = (stage * KS) & 1;                // fragment buffer holding this tile's k-step 0
+        // the LDS targets of this tile body's loads are formed here, one scalar add each, not kept
+        // in registers across the whole loop
+        asm volatile("" : "+s"(wave_lds));
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int cur = (parity + ks) & 1;
             const bool last = ks == KS - 1;
-            if (last && has_next) {
-                // fragments of this tile are all in registers (or being read from an older barrier's
-                // tile); tile kt+1 must be visible, and nobody may still read the stage that the
-                // next iteration's loads overwrite
-                if (more) tile_barrier<STEADY_VMCNT>();
-                else tile_barrier<0>();
-            }
-            const unsigned rbase = last ? next_base : stage_base;
+            // before the reads of tile kt+1 start: its loads have landed everywhere, and nobody still reads
+            // the stage that the next tile body's loads overwrite
+            if (last && has_next) tile_barrier<ALLOW>();
+            const int rstage = last ? next : stage;
             const int rks = last ? 0 : ks + 1;
             const bool do_read = !last || has_next;
 #pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                const int i = m / TN, j = m % TN;
-                acc[i][j] = E::mfma(fb[cur][j], fa[cur][i], acc[i][j]);
+            for (int g = 0; g < NM; ++g) {
+                const int i = g / TN, j = g % TN;
+                acc[i][j] = E::mfma(frag_b(cur, j), frag_a(cur, i), acc[i][j]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (do_read) {
 #pragma unroll
-                    for (int u = 0; u < NR; ++u) {
-                        // fragments in the order the next k-step first needs them: a0 b0 a1 b1 ..., then
-                        // the rest of the longer side; unit u goes behind MFMA (u * NM) / NR
-                        if (u < (m * NR) / NM || u >= ((m + 1) * NR) / NM) continue;
-                        constexpr int TMIN = TM < TN ? TM : TN;
-                        if (u < 2 * TMIN) {
-                            if (u % 2 == 0) fa[cur ^ 1][u / 2] = read_a(rbase, rks, u / 2);
-                            else fb[cur ^ 1][u / 2] = read_b(rbase, rks, u / 2);
-                        } else {
-                            const int r = u - TMIN;
-                            if (TM > TN) fa[cur ^ 1][r] = read_a(rbase, rks, r);
-                            else fb[cur ^ 1][r] = read_b(rbase, rks, r);
-                        }
+                    for (int r = 0; r < NRD; ++r) {
+                        if ((r * RG) / NRD != g) continue;
+                        read_piece(r, cur ^ 1, rstage, rks);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-                if (more && !TWO_STAGE) {
-                    const int f = ks * NM + m;
+                if (more) {
 #pragma unroll
-                    for (int idx = 0; idx < LPT; ++idx) {
-                        if (idx < (f * LPT) / TOT || idx >= ((f + 1) * LPT) / TOT) continue;
-                        issue_load(idx, pre);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-                if (more && TWO_STAGE && last) {
-#pragma unroll
-                    for (int idx = 0; idx < LPT; ++idx) {
-                        if (idx < (m * LPT) / NM || idx >= ((m + 1) * LPT) / NM) continue;
-                        issue_load(idx, pre);
+                    for (int l = 0; l < LPK; ++l) {
+                        if (((2 * l + 1) * NM) / (2 * LPK) != g) continue;
+                        issue_load(ks * LPK + l, pre);
+                        // behind an operand's last load of the tile: its pointer moves on
+                        if (ks * LPK + l == ATile::CPW - 1) advance_a();
+                        if (ks * LPK + l == LPT - 1) advance_b();
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
         }
-        if (more) next_tile();
-        stage = next;
     };
     {
         using T = std::true_type;
         using F = std::false_type;
-        using P0 = std::integral_constant<int, 0>;
-        using P1 = std::integral_constant<int, (KS & 1)>;   // parity of the second tile of a pair
-        // Straight-line phases only: selecting an instantiation at run time inside a loop makes the
-        // register allocator spill the accumulators.
-        int kt = 0;
-        if (UNROLL == 2) {
-            // odd KS: the fragment buffers alternate per K-tile, so tiles go in pairs (nk is even)
-            static_assert(UNROLL == 1 || NSTAGE == 4, "the pair schedule below is written for four stages");
-            for (; kt + NSTAGE < nk; kt += 2) {
-                k_tile(T{}, T{}, P0{});
-                k_tile(T{}, T{}, P1{});
-            }
-            if (nk - kt == 4) {
-                k_tile(T{}, T{}, P0{});
-                k_tile(F{}, T{}, P1{});
-            }
-            k_tile(F{}, T{}, P0{});
-            k_tile(F{}, F{}, P1{});
-        } else {
-            for (; kt + PRE < nk; ++kt) k_tile(T{}, T{}, P0{});
-            for (; kt + 1 < nk; ++kt) k_tile(F{}, T{}, P0{});
-            k_tile(F{}, F{}, P0{});
+        constexpr int STEADY = (NSTAGE - 3) * LPT + (KS - 1) * LPK;   // tiles after kt+1, and this body's loads so far
+        static_assert(NSTAGE == 4, "the pass over the stages below is written out for four stages");
+        const int passes = p.nk / NSTAGE;
+        for (int ps = 1; ps < passes; ++ps) {
+            k_tile(std::integral_constant<int, 0>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
+            k_tile(std::integral_constant<int, 1>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
+            k_tile(std::integral_constant<int, 2>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
+            k_tile(std::integral_constant<int, 3>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
         }
+        // last pass: one more tile to load, then the pipeline drains
+        k_tile(std::integral_constant<int, 0>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
+        k_tile(std::integral_constant<int, 1>{}, F{}, T{}, std::integral_constant<int, LPT>{});
+        k_tile(std::integral_constant<int, 2>{}, F{}, T{}, std::integral_constant<int, 0>{});
+        k_tile(std::integral_constant<int, 3>{}, F{}, F{}, std::integral_constant<int, 0>{});
     }
 
     // ---- epilogue: 32 rows at a time through a wave-private LDS strip -----------------------------------
@@ -544,17 +559,16 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     constexpr int LPR = WN * ESZ / 16;   // lanes per output row
     constexpr int RPP = 64 / LPR;        // rows per pass
     TOut *C;
-    const float *bias_lds = nullptr;     // MAPPED with a bias: the bias of this wavefront's first column
+    const float *bias_lds = nullptr;     // MAPPED: the bias of this wavefront's first column (zeros without a bias)
     if constexpr (!MAPPED) {
         C = static_cast<TOut *>(p.C) + batch * p.sC + split * p.sSplit + (m0 + wm * WM) * p.ldc + n0 + wn * WN;
     } else {
         C = static_cast<TOut *>(p.C) + axis_offset(p.maps.c_n, n0 + wn * WN + (lane % LPR) * (16 / ESZ));
-        if (p.maps.bias) {
-            float *strip = reinterpret_cast<float *>(smem + WAVES * EPI_BYTES);
-            for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias[axis_offset(p.maps.bias_n, n0 + x)];
-            __syncthreads();
-            bias_lds = strip + wn * WN + 4 * (lane >> 5);
-        }
+        // one add per output element whether or not there is a bias: no branch inside the unrolled loops
+        float *strip = reinterpret_cast<float *>(smem + WAVES * EPI_BYTES);
+        for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias ? p.maps.bias[axis_offset(p.maps.bias_n, n0 + x)] : 0.f;
+        __syncthreads();
+        bias_lds = strip + wn * WN + 4 * (lane >> 5);
     }
     const float alpha = p.alpha;
 #pragma unroll
@@ -568,10 +582,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 float v0 = acc[i][j][4 * g] * alpha, v1 = acc[i][j][4 * g + 1] * alpha;
                 float v2 = acc[i][j][4 * g + 2] * alpha, v3 = acc[i][j][4 * g + 3] * alpha;
                 if constexpr (MAPPED) {
-                    if (bias_lds) {
-                        const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
-                        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
-                    }
+                    const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
+                    v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
                 }
                 if (ESZ == 4) {
                     f32x4 v = {v0, v1, v2, v3};
@@ -624,6 +636,7 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
     p.tiles_m = (int)(g.Mo / BM);
     p.tiles_n = (int)(g.No / BN);
     p.nk = (int)(g.Kc * E::ELT / BKB / splits);
+    if (p.nk < NSTAGE || p.nk % NSTAGE != 0 || (int64_t)p.nk * splits * BKB != g.Kc * E::ELT) return CUBE3D_ENOTIMPL;
     p.group_m = 8;
     p.splits = splits;
     p.sSplit = out_split_stride;
