@@ -65,7 +65,7 @@ Plan make_plan(const GemmArgs &g)
     if (g.Kc % (4 * ktile)) return p;           // the K loop takes the four LDS stages per pass
     const int64_t nk = g.Kc / ktile;
     const bool fits256 = g.Mo % 256 == 0 && g.No % 256 == 0;
-    const bool fits128 = !fp8 && g.Mo % 128 == 0 && g.No % 128 == 0;
+    const bool fits128 = (!fp8 || (g.a_kmajor && g.b_kmajor)) && g.Mo % 128 == 0 && g.No % 128 == 0;
     if (!fits256 && !fits128) return p;
     const int64_t tiles256 = fits256 ? (g.Mo / 256) * (g.No / 256) * g.batch : 0;
     if (fits256 && (tiles256 >= (3 * NUM_CU) / 4 || !fits128)) p.tile = 256;
@@ -109,12 +109,23 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
-// 64-byte K-tiles, four LDS stages for every operand layout (deeper K-tiles leave room for two
-// stages only, whose loads then come in bursts that hold up the MFMA stream).
+// K-tile depth per operand layout (measured on config-4 shapes).  A K-major operand with 64-byte
+// K-tiles asks for every 128-byte cache line twice, one K-tile apart, and by then the line has left
+// the CU's vector L1: with both operands K-major (dX) that doubles the L2 -> L1 fill traffic and the
+// loads hold up the MFMA stream.  So dX takes 128-byte K-tiles, two stages; the layouts with a
+// transposed operand take 64-byte K-tiles, four stages (shorter prologue, more slack for the loads).
 template <typename E, int T, typename TOut>
 int launch_for_layout(const GemmArgs &g, int splits, void *out, int64_t ld, int64_t bs, int64_t ss)
 {
-    return launch_layout<E, T, T, 64, 4, TOut>(g, splits, out, ld, bs, ss, g.alpha);
+    if (g.a_kmajor && g.b_kmajor && T == 256 && (g.Kc * E::ELT / splits) % 256 == 0)
+        return launch_cfg<E, T, T, 128, 2, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
+    if constexpr (std::is_same<E, Fp8>::value && T == 128) {
+        // rows of 128 bytes are too short for the swizzle of an MN-major fp8 tile
+        if (!(g.a_kmajor && g.b_kmajor)) return CUBE3D_ENOTIMPL;
+        return launch_cfg<E, T, T, 64, 4, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
+    } else {
+        return launch_layout<E, T, T, 64, 4, TOut>(g, splits, out, ld, bs, ss, g.alpha);
+    }
 }
 
 template <typename E, int T, typename TOut> int run_tile(const GemmArgs &g, const Plan &pl)
@@ -146,8 +157,10 @@ int gemm_fast(const GemmArgs &g)
     if (pl.tile == 0) return CUBE3D_ENOTIMPL;
     if (g.maps) return gemm_fast_mapped(g, pl.tile);
     const bool f32 = g.out_dtype == CUBE3D_F32;
-    if (g.in_dtype == CUBE3D_FP8_E4M3)
-        return f32 ? run_tile<Fp8, 256, float>(g, pl) : run_tile<Fp8, 256, unsigned short>(g, pl);
+    if (g.in_dtype == CUBE3D_FP8_E4M3) {
+        if (pl.tile == 256) return f32 ? run_tile<Fp8, 256, float>(g, pl) : run_tile<Fp8, 256, unsigned short>(g, pl);
+        return f32 ? run_tile<Fp8, 128, float>(g, pl) : run_tile<Fp8, 128, unsigned short>(g, pl);
+    }
     if (pl.tile == 256) return f32 ? run_tile<Bf16, 256, float>(g, pl) : run_tile<Bf16, 256, unsigned short>(g, pl);
     return f32 ? run_tile<Bf16, 128, float>(g, pl) : run_tile<Bf16, 128, unsigned short>(g, pl);
 }

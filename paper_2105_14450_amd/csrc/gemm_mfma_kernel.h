@@ -256,7 +256,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     constexpr int EPI_BYTES = 32 * EPI_STRIDE;
     static_assert(KS >= 1 && BKB % (E::KSTEP * E::ELT) == 0, "K-tile must hold whole k-steps");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wavefront tile is made of 32x32 MFMA tiles");
-    static_assert(NSTAGE >= 3 && (NSTAGE * KS) % 2 == 0, "the fragment buffers alternate per k-step and must line up per pass over the stages");
+    static_assert((NSTAGE == 2 || NSTAGE == 4) && (NSTAGE * KS) % 2 == 0, "the fragment buffers alternate per k-step and must line up per pass over the stages");
+    static_assert(NSTAGE != 2 || KS >= 2, "the two-stage schedule loads in the first and in the last k-step of a tile");
     static_assert(LPT % KS == 0, "the loads of a K-tile are dealt out evenly over its k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
     static_assert(NSTAGE * STAGE_BYTES <= 2 * 65536, "an LDS address is one of two lane registers plus a 16-bit immediate");
@@ -467,15 +468,27 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // ---- pipeline prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed, its first fragments read --------
+    // ---- pipeline prologue: the first tiles in flight, tile 0 landed, its first fragments read ----------
+    if constexpr (NSTAGE == 2) {
+        // tile 0 whole, of tile 1 operand A only (see the two-stage schedule below)
 #pragma unroll
-    for (int s = 0; s < PRE; ++s) {
-#pragma unroll
-        for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
+        for (int idx = 0; idx < LPT; ++idx) issue_load(idx, 0);
         advance_a();
         advance_b();
+#pragma unroll
+        for (int idx = 0; idx < ATile::CPW; ++idx) issue_load(idx, 1);
+        advance_a();
+        tile_barrier<ATile::CPW>();
+    } else {
+#pragma unroll
+        for (int s = 0; s < PRE; ++s) {
+#pragma unroll
+            for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
+            advance_a();
+            advance_b();
+        }
+        tile_barrier<(PRE - 1) * LPT>();
     }
-    tile_barrier<(PRE - 1) * LPT>();
 #pragma unroll
     for (int r = 0; r < NRD; ++r) read_piece(r, 0, 0, 0);
 
@@ -484,11 +497,16 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // stage, fragment buffer and every address constant are fixed per copy of the tile body.  Per
     // k-step: NM MFMAs; behind MFMA g come the LDS reads of the following k-step that fall into gap g
     // (all of them inside the first RG gaps, so that they have landed when the tile barrier or the next
-    // k-step asks for them) and this k-step's share of the async loads of tile kt+NSTAGE-1.  The order
-    // is pinned with scheduling barriers.  ALLOW = loads that may stay in flight across the tile barrier.
+    // k-step asks for them) and this k-step's share of the async loads.  The order is pinned with
+    // scheduling barriers.  ALLOW = loads that may stay in flight across the tile barrier.
+    //   four stages: tile kt+3 is loaded during tile kt, its loads dealt out over all k-steps;
+    //   two stages (deeper K-tiles: whole cache lines per row of a K-major operand, half as many
+    //   barriers): the stage of tile kt is free behind the tile barrier, so operand A of tile kt+2 is
+    //   loaded in the last k-step of tile kt and operand B in the first k-step of tile kt+1, which
+    //   leaves them the k-steps in between to land.
     auto k_tile = [&](auto stage_c, auto more_c, auto has_next_c, auto allow_c) {
         constexpr int stage = decltype(stage_c)::value;
-        constexpr bool more = decltype(more_c)::value;          // tile kt+PRE exists: load it
+        constexpr bool more = decltype(more_c)::value;          // tile kt+NSTAGE-1 (two stages: kt+2) exists: load it
         constexpr bool has_next = decltype(has_next_c)::value;  // tile kt+1 exists
         constexpr int ALLOW = decltype(allow_c)::value;
         constexpr int pre = (stage + NSTAGE - 1) % NSTAGE;      // stage the loads of this tile body go to
@@ -520,7 +538,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-                if (more) {
+                if (NSTAGE > 2 && more) {
 #pragma unroll
                     for (int l = 0; l < LPK; ++l) {
                         if (((2 * l + 1) * NM) / (2 * LPK) != g) continue;
@@ -531,26 +549,59 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+                if (NSTAGE == 2 && ks == 0 && has_next) {
+#pragma unroll
+                    for (int l = 0; l < BTile::CPW; ++l) {
+                        if (((2 * l + 1) * NM) / (2 * BTile::CPW) != g) continue;
+                        issue_load(ATile::CPW + l, next);
+                        if (l == BTile::CPW - 1) advance_b();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if (NSTAGE == 2 && last && more) {
+#pragma unroll
+                    for (int l = 0; l < ATile::CPW; ++l) {
+                        if (((2 * l + 1) * NM) / (2 * ATile::CPW) != g) continue;
+                        issue_load(l, stage);
+                        if (l == ATile::CPW - 1) advance_a();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
         }
     };
     {
         using T = std::true_type;
         using F = std::false_type;
-        constexpr int STEADY = (NSTAGE - 3) * LPT + (KS - 1) * LPK;   // tiles after kt+1, and this body's loads so far
-        static_assert(NSTAGE == 4, "the pass over the stages below is written out for four stages");
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        using Z = std::integral_constant<int, 0>;
         const int passes = p.nk / NSTAGE;
-        for (int ps = 1; ps < passes; ++ps) {
-            k_tile(std::integral_constant<int, 0>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
-            k_tile(std::integral_constant<int, 1>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
-            k_tile(std::integral_constant<int, 2>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
-            k_tile(std::integral_constant<int, 3>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
+        if constexpr (NSTAGE == 2) {
+            // nothing is issued between the last load of tile kt+1 and the barrier that waits for it
+            for (int ps = 1; ps < passes; ++ps) {
+                k_tile(S0{}, T{}, T{}, Z{});
+                k_tile(S1{}, T{}, T{}, Z{});
+            }
+            k_tile(S0{}, F{}, T{}, Z{});
+            k_tile(S1{}, F{}, F{}, Z{});
+        } else {
+            using S2 = std::integral_constant<int, 2>;
+            using S3 = std::integral_constant<int, 3>;
+            // in flight across the barrier: tile kt+2, and what this tile body has issued of tile kt+3
+            using STEADY = std::integral_constant<int, LPT + (KS - 1) * LPK>;
+            for (int ps = 1; ps < passes; ++ps) {
+                k_tile(S0{}, T{}, T{}, STEADY{});
+                k_tile(S1{}, T{}, T{}, STEADY{});
+                k_tile(S2{}, T{}, T{}, STEADY{});
+                k_tile(S3{}, T{}, T{}, STEADY{});
+            }
+            // last pass: one more tile to load, then the pipeline drains
+            k_tile(S0{}, T{}, T{}, STEADY{});
+            k_tile(S1{}, F{}, T{}, std::integral_constant<int, LPT>{});
+            k_tile(S2{}, F{}, T{}, Z{});
+            k_tile(S3{}, F{}, F{}, Z{});
         }
-        // last pass: one more tile to load, then the pipeline drains
-        k_tile(std::integral_constant<int, 0>{}, T{}, T{}, std::integral_constant<int, STEADY>{});
-        k_tile(std::integral_constant<int, 1>{}, F{}, T{}, std::integral_constant<int, LPT>{});
-        k_tile(std::integral_constant<int, 2>{}, F{}, T{}, std::integral_constant<int, 0>{});
-        k_tile(std::integral_constant<int, 3>{}, F{}, F{}, std::integral_constant<int, 0>{});
     }
 
     // ---- epilogue: 32 rows at a time through a wave-private LDS strip -----------------------------------
