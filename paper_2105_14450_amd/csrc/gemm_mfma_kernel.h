@@ -221,7 +221,8 @@ struct Params {
     int64_t sA, sB, sC;
     int tiles_m, tiles_n, nk;   // nk = K-tiles per workgroup
     int group_m;
-    int splits;                 // split-K: blockIdx.y = batch * splits + split; split s takes K-tiles [s*nk, (s+1)*nk)
+    int splits;                 // split-K: y = batch * splits + split; split s takes K-tiles [s*nk, (s+1)*nk)
+    int y_items;                // batch * splits: an item is (y, output tile), item number = y * tiles + tile
     int64_t sSplit;             // output distance between the partial results of consecutive splits (elements)
     float alpha;
     // MAPPED instantiations only (then lda / ldb / ldc, the strides and the splits are unused)
@@ -252,8 +253,16 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     constexpr int NBB = BKM ? KS * E::PK : TN;
     constexpr int PRE = NSTAGE - 1;                    // tiles in flight after the prologue
     constexpr int ESZ = sizeof(TOut);
-    constexpr int EPI_STRIDE = WN * ESZ + 16;
+    // Epilogue staging: a wave-private strip of 32 rows x JH 32-column blocks.  The large tiles keep it
+    // behind the stage buffers (the CU's LDS is theirs alone), so that the loads of the next item can
+    // already fill the stages while this item is written out; the small tiles (two workgroups per CU)
+    // reuse the stage memory.
+    constexpr bool EPI_SEPARATE = BM * BN > 128 * 128;
+    constexpr int JH = EPI_SEPARATE ? (TN * 32 * ESZ > 128 ? 128 / (32 * ESZ) : TN) : TN;
+    constexpr int EPI_STRIDE = JH * 32 * ESZ + 16;
     constexpr int EPI_BYTES = 32 * EPI_STRIDE;
+    constexpr int EPI_BASE = EPI_SEPARATE ? NSTAGE * STAGE_BYTES : 0;
+    static_assert(TN % JH == 0, "whole strips");
     static_assert(KS >= 1 && BKB % (E::KSTEP * E::ELT) == 0, "K-tile must hold whole k-steps");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wavefront tile is made of 32x32 MFMA tiles");
     static_assert((NSTAGE == 2 || NSTAGE == 4) && (NSTAGE * KS) % 2 == 0, "the fragment buffers alternate per k-step and must line up per pass over the stages");
@@ -261,23 +270,32 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     static_assert(LPT % KS == 0, "the loads of a K-tile are dealt out evenly over its k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
     static_assert(NSTAGE * STAGE_BYTES <= 2 * 65536, "an LDS address is one of two lane registers plus a 16-bit immediate");
-    static_assert(WAVES * EPI_BYTES + BN * 4 <= NSTAGE * STAGE_BYTES, "epilogue staging (and the bias strip) must fit");
+    static_assert(EPI_BASE + WAVES * EPI_BYTES + BN * 4 <= (EPI_SEPARATE ? 160 * 1024 : NSTAGE * STAGE_BYTES),
+                  "epilogue staging (and the bias strip) must fit");
     static_assert((NSTAGE - 2) * LPT <= 63, "vmcnt range");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
+    const int lane = tid & 63, lane_id = lane;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- which output tile: consecutive ids go to different XCDs (id mod 8), so regroup them so
-    //      that the tiles one XCD runs together form a compact patch of the tile grid (shared L2)
-    int tile = blockIdx.x;
-    {
-        const int total = p.tiles_m * p.tiles_n;
-        if (total % 8 == 0) tile = (tile % 8) * (total / 8) + tile / 8;
+    // ---- work items ------------------------------------------------------------------------------------
+    // The workgroups are persistent: workgroup w takes the items w, w + gridDim.x, ...  An item is one
+    // output tile of one (batch, split).  Consecutive workgroup ids go to different XCDs (id mod 8), and
+    // gridDim.x is a multiple of 8 whenever a workgroup gets more than one item, so an item's number mod 8
+    // names its XCD too: the numbers are regrouped so that the tiles one XCD runs together form a compact
+    // patch of the tile grid (shared L2).
+    const int tiles_total = p.tiles_m * p.tiles_n;
+    const int items = tiles_total * p.y_items;
+    int64_t m0, n0;            // origin of the item whose operands are being loaded
+    int batch, split;
+    auto decode_item = [&](int item) {
+        const int y = item / tiles_total;
+        int tile = item - y * tiles_total;
+        if (tiles_total % 8 == 0) tile = (tile % 8) * (tiles_total / 8) + tile / 8;
         const int per_group = p.group_m * p.tiles_n;
         const int gid = tile / per_group;
         const int first_m = gid * p.group_m;
@@ -285,12 +303,11 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         const int in_group = tile - gid * per_group;
         const int tm_ = first_m + in_group % gsz;
         const int tn_ = in_group / gsz;
-        tile = tm_ * p.tiles_n + tn_;
-    }
-    const int tile_m = tile / p.tiles_n, tile_n = tile % p.tiles_n;
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int batch = blockIdx.y / p.splits;
-    const int split = blockIdx.y - batch * p.splits;
+        m0 = (int64_t)tm_ * BM;
+        n0 = (int64_t)tn_ * BN;
+        batch = y / p.splits;
+        split = y - batch * p.splits;
+    };
 
     // ---- global sources of this lane's async loads: one scalar pointer per operand, standing on the
     //      K-tile that is loaded next, plus one 32-bit byte offset per load that never changes
@@ -298,6 +315,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     unsigned a_voff[ATile::CPW], b_voff[BTile::CPW];
     int64_t a_step = 0, b_step = 0;              // bytes from one K-tile to the next (plain operands)
     int a_c1 = 0, a_c2 = 0, b_c1 = 0, b_c2 = 0;  // MAPPED: position of the K walk inside the current block / shard
+    auto setup_sources = [&]() {
     if constexpr (!MAPPED) {
         const int64_t kt0 = (int64_t)split * p.nk;   // first K-tile of this split
         a_step = ATile::ktile_step(p.lda) * E::ELT;
@@ -316,6 +334,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         constexpr int EPS = 16 / E::ELT;   // elements per 16-byte slot
         a_base = static_cast<const char *>(p.A);
         b_base = static_cast<const char *>(p.B);
+        a_c1 = a_c2 = b_c1 = b_c2 = 0;
         {
             const int first = wave * ATile::RPC + lane / ATile::SPR;   // tile row (K-major) or k-row (MN-major)
 #pragma unroll
@@ -347,6 +366,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             }
         }
     }
+    };
 
     // async load number idx of the K-tile the scalar pointers stand on, into LDS stage `stage`
     // (idx and stage are constants wherever this is called: the LDS address is wave base + constant)
@@ -461,36 +481,44 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     };
 
     f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // ---- pipeline prologue: the first tiles in flight, tile 0 landed, its first fragments read ----------
-    if constexpr (NSTAGE == 2) {
-        // tile 0 whole, of tile 1 operand A only (see the two-stage schedule below)
+    // ---- pipeline prologue of an item, in two parts -----------------------------------------------------
+    // early: the loads that go to stages which nobody reads any more once this wavefront has left the K
+    // loop of the previous item (all stages but the one of its last K-tile); late: the rest, behind a
+    // workgroup barrier.  Four stages: tiles 0..2 are all early.  Two stages: tile 0 early, operand A of
+    // tile 1 late (operand B of tile 1 follows in the first k-step, see the schedule below).
+    auto early_loads = [&]() {
+        if constexpr (NSTAGE == 2) {
 #pragma unroll
-        for (int idx = 0; idx < LPT; ++idx) issue_load(idx, 0);
-        advance_a();
-        advance_b();
-#pragma unroll
-        for (int idx = 0; idx < ATile::CPW; ++idx) issue_load(idx, 1);
-        advance_a();
-        tile_barrier<ATile::CPW>();
-    } else {
-#pragma unroll
-        for (int s = 0; s < PRE; ++s) {
-#pragma unroll
-            for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
+            for (int idx = 0; idx < LPT; ++idx) issue_load(idx, 0);
             advance_a();
             advance_b();
-        }
-        tile_barrier<(PRE - 1) * LPT>();
-    }
+        } else {
 #pragma unroll
-    for (int r = 0; r < NRD; ++r) read_piece(r, 0, 0, 0);
+            for (int s = 0; s < PRE; ++s) {
+#pragma unroll
+                for (int idx = 0; idx < LPT; ++idx) issue_load(idx, s);
+                advance_a();
+                advance_b();
+            }
+        }
+    };
+    // `stores`: global stores of the previous item's epilogue issued behind the early loads; they stay in
+    // flight (memory operations of a wavefront complete in the order they were issued)
+    auto finish_prologue = [&](auto stores_c) {
+        constexpr int stores = decltype(stores_c)::value;
+        if constexpr (NSTAGE == 2) {
+            __builtin_amdgcn_s_barrier();   // everyone has left the last K-tile of the previous item
+#pragma unroll
+            for (int idx = 0; idx < ATile::CPW; ++idx) issue_load(idx, 1);
+            advance_a();
+            tile_barrier<(ATile::CPW + stores <= 63 ? ATile::CPW + stores : 63)>();
+        } else {
+            tile_barrier<((PRE - 1) * LPT + stores <= 63 ? (PRE - 1) * LPT + stores : 63)>();
+        }
+#pragma unroll
+        for (int r = 0; r < NRD; ++r) read_piece(r, 0, 0, 0);
+    };
 
     // ---- main loop ----------------------------------------------------------------------------------
     // K-tile number kt lives in stage kt mod NSTAGE; one pass of the loop body takes NSTAGE tiles, so
@@ -504,8 +532,9 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     //   barriers): the stage of tile kt is free behind the tile barrier, so operand A of tile kt+2 is
     //   loaded in the last k-step of tile kt and operand B in the first k-step of tile kt+1, which
     //   leaves them the k-steps in between to land.
-    auto k_tile = [&](auto stage_c, auto more_c, auto has_next_c, auto allow_c) {
+    auto k_tile = [&](auto stage_c, auto more_c, auto has_next_c, auto allow_c, auto first_c) {
         constexpr int stage = decltype(stage_c)::value;
+        constexpr bool first = decltype(first_c)::value;        // first K-tile of the item: its first k-step starts the sums
         constexpr bool more = decltype(more_c)::value;          // tile kt+NSTAGE-1 (two stages: kt+2) exists: load it
         constexpr bool has_next = decltype(has_next_c)::value;  // tile kt+1 exists
         constexpr int ALLOW = decltype(allow_c)::value;
@@ -528,7 +557,14 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
 #pragma unroll
             for (int g = 0; g < NM; ++g) {
                 const int i = g / TN, j = g % TN;
-                acc[i][j] = E::mfma(frag_b(cur, j), frag_a(cur, i), acc[i][j]);
+                if (first && ks == 0) {
+                    f32x16 zero;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                    acc[i][j] = E::mfma(frag_b(cur, j), frag_a(cur, i), zero);
+                } else {
+                    acc[i][j] = E::mfma(frag_b(cur, j), frag_a(cur, i), acc[i][j]);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 if (do_read) {
 #pragma unroll
@@ -570,7 +606,9 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             }
         }
     };
-    {
+    // The accumulators are not cleared: the first k-step of an item's first K-tile starts the sums from
+    // a zero operand.  That tile body exists in two copies (more K-tiles than one pass or not).
+    auto k_loop = [&]() {
         using T = std::true_type;
         using F = std::false_type;
         using S0 = std::integral_constant<int, 0>;
@@ -579,84 +617,159 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         const int passes = p.nk / NSTAGE;
         if constexpr (NSTAGE == 2) {
             // nothing is issued between the last load of tile kt+1 and the barrier that waits for it
-            for (int ps = 1; ps < passes; ++ps) {
-                k_tile(S0{}, T{}, T{}, Z{});
-                k_tile(S1{}, T{}, T{}, Z{});
+            if (passes > 1) {
+                k_tile(S0{}, T{}, T{}, Z{}, T{});
+                k_tile(S1{}, T{}, T{}, Z{}, F{});
+                for (int ps = 2; ps < passes; ++ps) {
+                    k_tile(S0{}, T{}, T{}, Z{}, F{});
+                    k_tile(S1{}, T{}, T{}, Z{}, F{});
+                }
+                k_tile(S0{}, F{}, T{}, Z{}, F{});
+            } else {
+                k_tile(S0{}, F{}, T{}, Z{}, T{});
             }
-            k_tile(S0{}, F{}, T{}, Z{});
-            k_tile(S1{}, F{}, F{}, Z{});
+            k_tile(S1{}, F{}, F{}, Z{}, F{});
         } else {
             using S2 = std::integral_constant<int, 2>;
             using S3 = std::integral_constant<int, 3>;
             // in flight across the barrier: tile kt+2, and what this tile body has issued of tile kt+3
             using STEADY = std::integral_constant<int, LPT + (KS - 1) * LPK>;
-            for (int ps = 1; ps < passes; ++ps) {
-                k_tile(S0{}, T{}, T{}, STEADY{});
-                k_tile(S1{}, T{}, T{}, STEADY{});
-                k_tile(S2{}, T{}, T{}, STEADY{});
-                k_tile(S3{}, T{}, T{}, STEADY{});
+            if (passes > 1) {
+                k_tile(S0{}, T{}, T{}, STEADY{}, T{});
+                k_tile(S1{}, T{}, T{}, STEADY{}, F{});
+                k_tile(S2{}, T{}, T{}, STEADY{}, F{});
+                k_tile(S3{}, T{}, T{}, STEADY{}, F{});
+                for (int ps = 2; ps < passes; ++ps) {
+                    k_tile(S0{}, T{}, T{}, STEADY{}, F{});
+                    k_tile(S1{}, T{}, T{}, STEADY{}, F{});
+                    k_tile(S2{}, T{}, T{}, STEADY{}, F{});
+                    k_tile(S3{}, T{}, T{}, STEADY{}, F{});
+                }
+                k_tile(S0{}, T{}, T{}, STEADY{}, F{});
+            } else {
+                k_tile(S0{}, T{}, T{}, STEADY{}, T{});
             }
-            // last pass: one more tile to load, then the pipeline drains
-            k_tile(S0{}, T{}, T{}, STEADY{});
-            k_tile(S1{}, F{}, T{}, std::integral_constant<int, LPT>{});
-            k_tile(S2{}, F{}, T{}, Z{});
-            k_tile(S3{}, F{}, F{}, Z{});
+            // rest of the last pass: the pipeline drains
+            k_tile(S1{}, F{}, T{}, std::integral_constant<int, LPT>{}, F{});
+            k_tile(S2{}, F{}, T{}, Z{}, F{});
+            k_tile(S3{}, F{}, F{}, Z{}, F{});
         }
-    }
+    };
 
-    // ---- epilogue: 32 rows at a time through a wave-private LDS strip -----------------------------------
-    __syncthreads();   // all fragment reads of the stage buffers are done
-    char *epi = smem + wave * EPI_BYTES;
-    constexpr int LPR = WN * ESZ / 16;   // lanes per output row
-    constexpr int RPP = 64 / LPR;        // rows per pass
-    TOut *C;
-    const float *bias_lds = nullptr;     // MAPPED: the bias of this wavefront's first column (zeros without a bias)
-    if constexpr (!MAPPED) {
-        C = static_cast<TOut *>(p.C) + batch * p.sC + split * p.sSplit + (m0 + wm * WM) * p.ldc + n0 + wn * WN;
-    } else {
-        C = static_cast<TOut *>(p.C) + axis_offset(p.maps.c_n, n0 + wn * WN + (lane % LPR) * (16 / ESZ));
-        // one add per output element whether or not there is a bias: no branch inside the unrolled loops
-        float *strip = reinterpret_cast<float *>(smem + WAVES * EPI_BYTES);
-        for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias ? p.maps.bias[axis_offset(p.maps.bias_n, n0 + x)] : 0.f;
-        __syncthreads();
-        bias_lds = strip + wn * WN + 4 * (lane >> 5);
-    }
-    const float alpha = p.alpha;
+    // ---- epilogue: 32 rows x JH column blocks at a time through a wave-private LDS strip --------------------
+    constexpr int LPR = JH * 32 * ESZ / 16;   // lanes per strip row
+    constexpr int RPP = 64 / LPR;             // rows per pass
+    constexpr int STORES = TM * (TN / JH) * (32 / RPP);   // global stores per wavefront
+    auto epilogue_impl = [&](auto scaled_c, int64_t em0, int64_t en0, int ebatch, int esplit) {
+        constexpr bool scaled = decltype(scaled_c)::value;   // alpha != 1: one more multiply per element
+        // The lane number and the row stride are made opaque here, so that the strip and row addresses
+        // below are formed inside the epilogue: hoisted out of the item loop they would occupy
+        // registers (and spill) through the whole K loop.
+        int lane = lane_id;
+        asm volatile("" : "+v"(lane));
+        char *epi = smem + EPI_BASE + wave * EPI_BYTES;
+        TOut *C;
+        const float *bias_lds = nullptr;     // MAPPED: the bias of this wavefront's first column (zeros without a bias)
+        if constexpr (!MAPPED) {
+            C = static_cast<TOut *>(p.C) + ebatch * p.sC + esplit * p.sSplit + (em0 + wm * WM) * p.ldc + en0 + wn * WN;
+        } else {
+            C = static_cast<TOut *>(p.C);
+            // one add per output element whether or not there is a bias: no branch inside the unrolled loops
+            float *strip = reinterpret_cast<float *>(smem + EPI_BASE + WAVES * EPI_BYTES);
+            __syncthreads();   // the previous item's strip has been read
+            for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias ? p.maps.bias[axis_offset(p.maps.bias_n, en0 + x)] : 0.f;
+            __syncthreads();
+            bias_lds = strip + wn * WN + 4 * (lane >> 5);
+        }
+        const float alpha = p.alpha;
+        int64_t row_stride = MAPPED ? p.maps.c_m.u : p.ldc;
+        asm volatile("" : "+s"(row_stride));
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i) {
+            int64_t strip_m = 0;   // MAPPED: where this 32-row strip (inside one shard) starts
+            if constexpr (MAPPED) strip_m = axis_offset(p.maps.c_m, em0 + wm * WM + i * 32);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+            for (int jh = 0; jh < TN / JH; ++jh) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                // registers 4g..4g+3 of lane: row lane%32, columns j*32 + 8g + 4*(lane/32) + 0..3
-                char *dst = epi + (lane & 31) * EPI_STRIDE + (j * 32 + 8 * g + 4 * (lane >> 5)) * ESZ;
-                float v0 = acc[i][j][4 * g] * alpha, v1 = acc[i][j][4 * g + 1] * alpha;
-                float v2 = acc[i][j][4 * g + 2] * alpha, v3 = acc[i][j][4 * g + 3] * alpha;
-                if constexpr (MAPPED) {
-                    const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
-                    v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+                for (int jj = 0; jj < JH; ++jj) {
+                    const int j = jh * JH + jj;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        // registers 4g..4g+3 of lane: row lane%32, columns j*32 + 8g + 4*(lane/32) + 0..3
+                        char *dst = epi + (lane & 31) * EPI_STRIDE + (jj * 32 + 8 * g + 4 * (lane >> 5)) * ESZ;
+                        float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1];
+                        float v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
+                        if (scaled) { v0 *= alpha; v1 *= alpha; v2 *= alpha; v3 *= alpha; }
+                        if constexpr (MAPPED) {
+                            const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
+                            v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+                        }
+                        if (ESZ == 4) {
+                            f32x4 v = {v0, v1, v2, v3};
+                            *reinterpret_cast<f32x4 *>(dst) = v;
+                        } else {
+                            uint2 v;
+                            v.x = pack_bf16x2(v0, v1);
+                            v.y = pack_bf16x2(v2, v3);
+                            *reinterpret_cast<uint2 *>(dst) = v;
+                        }
+                    }
                 }
-                if (ESZ == 4) {
-                    f32x4 v = {v0, v1, v2, v3};
-                    *reinterpret_cast<f32x4 *>(dst) = v;
-                } else {
-                    uint2 v;
-                    v.x = pack_bf16x2(v0, v1);
-                    v.y = pack_bf16x2(v2, v3);
-                    *reinterpret_cast<uint2 *>(dst) = v;
+                int64_t col = 0;   // MAPPED: where this lane's 16 bytes of the strip row go
+                if constexpr (MAPPED) col = axis_offset(p.maps.c_n, en0 + wn * WN + jh * JH * 32 + (lane % LPR) * (16 / ESZ));
+#pragma unroll
+                for (int pass = 0; pass < 32 / RPP; ++pass) {
+                    const int row = pass * RPP + lane / LPR;
+                    const i32x4 v = *reinterpret_cast<const i32x4 *>(epi + row * EPI_STRIDE + (lane % LPR) * 16);
+                    char *gp;
+                    if constexpr (!MAPPED)
+                        gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * row_stride + jh * JH * 32) + (lane % LPR) * 16;
+                    else gp = reinterpret_cast<char *>(C + col + strip_m + (int64_t)row * row_stride);
+                    *reinterpret_cast<i32x4 *>(gp) = v;
                 }
+                // one strip at a time: without this the scheduler pulls all accumulator reads to the
+                // front and needs a register for every output element at once
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        int64_t strip = 0;   // MAPPED: where this 32-row strip (inside one shard) starts
-        if constexpr (MAPPED) strip = axis_offset(p.maps.c_m, m0 + wm * WM + i * 32);
-#pragma unroll
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
-            const int row = pass * RPP + lane / LPR;
-            const i32x4 v = *reinterpret_cast<const i32x4 *>(epi + row * EPI_STRIDE + (lane % LPR) * 16);
-            char *gp;
-            if constexpr (!MAPPED) gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * p.ldc) + (lane % LPR) * 16;
-            else gp = reinterpret_cast<char *>(C + strip + (int64_t)row * p.maps.c_m.u);
-            *reinterpret_cast<i32x4 *>(gp) = v;
+    };
+
+    auto epilogue = [&](int64_t em0, int64_t en0, int ebatch, int esplit) {
+        if (p.alpha == 1.f) epilogue_impl(std::false_type{}, em0, en0, ebatch, esplit);
+        else epilogue_impl(std::true_type{}, em0, en0, ebatch, esplit);
+    };
+
+    // ---- the items of this workgroup ----------------------------------------------------------------------
+    int item = blockIdx.x;
+    decode_item(item);
+    setup_sources();
+    early_loads();
+    finish_prologue(std::integral_constant<int, 0>{});
+    while (true) {
+        k_loop();
+        const int64_t em0 = m0, en0 = n0;
+        const int ebatch = batch, esplit = split;
+        item += gridDim.x;
+        const bool again = item < items;
+        if constexpr (EPI_SEPARATE) {
+            // the operands of the next item start to arrive while this one is written out
+            if (again) {
+                decode_item(item);
+                setup_sources();
+                early_loads();
+            }
+            epilogue(em0, en0, ebatch, esplit);
+            if (!again) break;
+            finish_prologue(std::integral_constant<int, STORES>{});
+        } else {
+            __syncthreads();   // all fragment reads of the stage buffers are done
+            epilogue(em0, en0, ebatch, esplit);
+            if (!again) break;
+            __syncthreads();   // ... and all reads of the staging strips
+            decode_item(item);
+            setup_sources();
+            early_loads();
+            finish_prologue(std::integral_constant<int, STORES>{});
         }
     }
 }
@@ -669,7 +782,9 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
 {
     using ATile = typename std::conditional<AK, KMajorTile<E, BM, BKB>, MNMajorTile<E, BM, BKB>>::type;
     using BTile = typename std::conditional<BKM, KMajorTile<E, BN, BKB>, MNMajorTile<E, BN, BKB>>::type;
-    constexpr int LDS = NSTAGE * (ATile::BYTES + BTile::BYTES);
+    constexpr bool BIG = BM * BN > 128 * 128;
+    // stage buffers; the large tiles add the epilogue staging (and the bias strip) behind them
+    constexpr int LDS = NSTAGE * (ATile::BYTES + BTile::BYTES) + (BIG ? 32 * 1024 : 0);
     auto kern = gemm_mfma_kernel<E, BM, BN, BKB, NSTAGE, AK, BKM, TOut, MAPPED>;
     static bool configured = false;
     if (!configured) {
@@ -697,7 +812,12 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
         p.ka = make_kwalk(g.maps->a_k, BKB / E::ELT);
         p.kb = make_kwalk(g.maps->b_k, BKB / E::ELT);
     }
-    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)(g.batch * splits), 1);
+    p.y_items = g.batch * splits;
+    // persistent workgroups: as many as the chip holds at once (a multiple of 8), or one per item
+    const int64_t items = (int64_t)p.tiles_m * p.tiles_n * p.y_items;
+    const int64_t resident = 256 * (BIG ? 1 : 2);
+    if (items >= (1ll << 31)) return CUBE3D_ENOTIMPL;
+    dim3 grid((unsigned)(items < resident ? items : resident), 1, 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), LDS, g.stream, p);
     return launch_status();
 }
