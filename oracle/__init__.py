@@ -10,6 +10,9 @@ matmul    the three plain products (Section 3.1.2, first differentiation
           formula), fp64, via the C file ``cube3d_oracle.c``
 layout    the load-balanced storage of Section 3.1.1 and the all-gather /
           reduce-scatter steps of Algorithms 1 and 2, as numpy slicing
+dist3d    the three matrix-product forms of Section 3.1.2 on the cube, forward and
+          backward (Algorithms 1-6), for any placement of the matrices, as numpy
+          slicing around the triple loops of ``matmul``
 numfmt    decoding of bf16 / fp8-e4m3 bit patterns to fp64 and the single
           round-to-nearest-even of an fp64 result to the compared dtype
 """
