@@ -263,6 +263,83 @@ int virtual_cube_linear_bwd_dx(const cube3d_desc *desc, const void *dY_shards, c
 int virtual_cube_linear_bwd_dw(const cube3d_desc *desc, const void *X_shards, const void *dY_shards, void *dW_shards,
                                void *stream);
 
+/*
+ * The three matrix-product forms of Section 3.1.2 on the cube: C = A B, C = A B^T, C = A^T B
+ * (Algorithms 1, 3, 5) and their backward passes (Algorithms 2, 4, 6), for matrices placed
+ * anywhere on the cube.  Every algorithm is the same four steps: all-gather the first
+ * operand, all-gather the second, multiply locally, reduce-scatter the result; a backward
+ * algorithm is two such products with the directions permuted (the three differentiation
+ * formulas of Section 3.1.2).  The calls below are those steps; the caller strings them
+ * together with the placements of its matrices.
+ *
+ * Placement of a [rows, cols] matrix (Section 3.1.1, generalised from the three cases printed
+ * there): the matrix is cut into q x q blocks; the processor's index along `row_axis` picks
+ * the block row, its index along `col_axis` the block column, and along the remaining
+ * direction each block is cut once more into q pieces, by rows (CUBE3D_SPLIT_ROWS: pieces
+ * [rows/q^2, cols/q]) or by columns (CUBE3D_SPLIT_COLS: pieces [rows/q, cols/q^2]).  The paper's
+ * A_ijl is (x, z, rows), B_lji is (z, y, cols), C_ilj is (x, y, rows).  The all-gather of a
+ * matrix and the reduce-scatter of a result run along the remaining direction.  Requires
+ * row_axis != col_axis, q^2 | rows and q | cols (rows split) or q | rows and q^2 | cols.
+ *
+ * virtual_cube_matrix_scatter / _assemble: full row-major matrix <-> cube buffer of pieces.
+ * virtual_cube_matrix_gather: cube buffer of pieces -> cube buffer of whole blocks
+ *   [rows/q, cols/q], pieces in index order.  Bit-for-bit copies of `dtype` elements.
+ * virtual_cube_matrix_reduce_scatter: cube buffer of partial blocks [rows/q, cols/q] of
+ *   `partial_dtype` (F32 or BF16) -> cube buffer of pieces of m->dtype (F32 or BF16): sum over
+ *   the q processors of the remaining direction in fp32, ascending index, one rounding; the
+ *   processor with index s keeps piece s.
+ */
+typedef enum cube3d_split {
+    CUBE3D_SPLIT_ROWS = 0,
+    CUBE3D_SPLIT_COLS = 1
+} cube3d_split;
+
+typedef struct cube3d_matrix {
+    int32_t q;
+    int32_t row_axis;       /* cube3d_axis */
+    int32_t col_axis;       /* cube3d_axis */
+    int32_t split;          /* cube3d_split */
+    int64_t rows, cols;     /* global sizes */
+    int32_t dtype;          /* storage type of the pieces (and of the blocks of a gather) */
+} cube3d_matrix;
+
+int virtual_cube_matrix_scatter(const cube3d_matrix *m, const void *full, void *pieces, void *stream);
+int virtual_cube_matrix_assemble(const cube3d_matrix *m, const void *pieces, void *full, void *stream);
+int virtual_cube_matrix_gather(const cube3d_matrix *m, const void *pieces, void *blocks, void *stream);
+int virtual_cube_matrix_reduce_scatter(const cube3d_matrix *m, int partial_dtype, const void *partials, void *pieces,
+                                       void *stream);
+
+/*
+ * Step 3 of Algorithms 1, 3, 5 (and of each line of Algorithms 2, 4, 6) for all q^3 processors
+ * in one batched launch: C_r = op(A_r, B_r) on the gathered blocks of processor r.
+ *   form = CUBE3D_FORM_AB  : A blocks [m, k], B blocks [k, n]
+ *   form = CUBE3D_FORM_ABT : A blocks [m, k], B blocks [n, k]
+ *   form = CUBE3D_FORM_ATB : A blocks [k, m], B blocks [k, n]
+ * -> C blocks [m, n] of out_dtype (F32 or BF16), fp32 accumulation, multiplied by
+ * scale_a * scale_b when in_dtype is CUBE3D_FP8_E4M3 (scales ignored otherwise).  m, n, k are
+ * the BLOCK sizes.  All buffers are cube buffers (block r belongs to processor r).
+ * `workspace`: at least cube3d_matmul_workspace_bytes() bytes of device scratch (may be NULL when
+ * that is 0), else CUBE3D_EWORKSPACE.
+ */
+typedef enum cube3d_form {
+    CUBE3D_FORM_AB = 0,
+    CUBE3D_FORM_ABT = 1,
+    CUBE3D_FORM_ATB = 2
+} cube3d_form;
+
+typedef struct cube3d_matmul {
+    int32_t q;
+    int32_t form;           /* cube3d_form */
+    int64_t m, n, k;        /* block sizes: result block [m, n], contraction length k */
+    int32_t in_dtype;
+    int32_t out_dtype;
+    float scale_a, scale_b;
+} cube3d_matmul;
+
+size_t cube3d_matmul_workspace_bytes(const cube3d_matmul *mm);
+int cube3d_matmul_blocks(const cube3d_matmul *mm, const void *A_blocks, const void *B_blocks, void *C_blocks,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 const char *cube3d_status_string(int status);
 int cube3d_version(void);
 

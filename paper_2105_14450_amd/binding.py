@@ -16,6 +16,8 @@ F32, BF16, FP8_E4M3 = 0, 1, 2
 AXIS_X, AXIS_Y, AXIS_Z = 0, 1, 2
 OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW, OPERAND_BIAS = range(7)
 OP_FWD, OP_BWD_DX, OP_BWD_DW, OP_BIAS_BWD = 0, 1, 2, 3
+SPLIT_ROWS, SPLIT_COLS = 0, 1
+FORM_AB, FORM_ABT, FORM_ATB = 0, 1, 2
 ALL_RANKS = (-1, -1, -1)
 
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "fp8_e4m3": FP8_E4M3}
@@ -37,6 +39,29 @@ def make_desc(q, M, K, N, in_dtype=BF16, out_dtype=F32, shard_dtype=None, in_axi
     if shard_dtype is None:
         shard_dtype = F32 if in_dtype == F32 else BF16
     return Desc(q, in_axis, M, K, N, in_dtype, out_dtype, shard_dtype, scale_x, scale_w, scale_dy)
+
+
+class Matrix(ctypes.Structure):
+    """Mirror of ``cube3d_matrix``: a [rows, cols] matrix placed on the cube."""
+    _fields_ = [("q", ctypes.c_int32), ("row_axis", ctypes.c_int32), ("col_axis", ctypes.c_int32),
+                ("split", ctypes.c_int32), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("dtype", ctypes.c_int32)]
+
+
+class Matmul(ctypes.Structure):
+    """Mirror of ``cube3d_matmul``: the batched local product of the q^3 processors."""
+    _fields_ = [("q", ctypes.c_int32), ("form", ctypes.c_int32),
+                ("m", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
+                ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("scale_a", ctypes.c_float), ("scale_b", ctypes.c_float)]
+
+
+def make_matrix(q, rows, cols, row_axis, col_axis, split, dtype) -> Matrix:
+    return Matrix(q, row_axis, col_axis, split, rows, cols, dtype)
+
+
+def make_matmul(q, form, m, n, k, in_dtype=BF16, out_dtype=F32, scale_a=1.0, scale_b=1.0) -> Matmul:
+    return Matmul(q, form, m, n, k, in_dtype, out_dtype, scale_a, scale_b)
 
 
 class Cube3DError(RuntimeError):
@@ -88,6 +113,17 @@ def load():
     lib.virtual_cube_linear_bwd_dx.restype = ci
     lib.virtual_cube_linear_bwd_dw.argtypes = [dp, vp, vp, vp, vp]
     lib.virtual_cube_linear_bwd_dw.restype = ci
+    mp, pp = ctypes.POINTER(Matrix), ctypes.POINTER(Matmul)
+    for name in ("virtual_cube_matrix_scatter", "virtual_cube_matrix_assemble", "virtual_cube_matrix_gather"):
+        f = getattr(lib, name)
+        f.argtypes = [mp, vp, vp, vp]
+        f.restype = ci
+    lib.virtual_cube_matrix_reduce_scatter.argtypes = [mp, ci, vp, vp, vp]
+    lib.virtual_cube_matrix_reduce_scatter.restype = ci
+    lib.cube3d_matmul_workspace_bytes.argtypes = [pp]
+    lib.cube3d_matmul_workspace_bytes.restype = sz
+    lib.cube3d_matmul_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.cube3d_matmul_blocks.restype = ci
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
     lib.cube3d_version.restype = ci
@@ -99,7 +135,9 @@ EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", 
            "virtual_cube_gather", "virtual_cube_reduce_scatter", "virtual_cube_scatter",
            "virtual_cube_assemble", "virtual_cube_bias_gather", "virtual_cube_reduce_scatter_bias",
            "virtual_cube_bias_bwd", "virtual_cube_linear_fwd", "virtual_cube_linear_bwd_dx",
-           "virtual_cube_linear_bwd_dw", "cube3d_status_string", "cube3d_version")
+           "virtual_cube_linear_bwd_dw", "virtual_cube_matrix_scatter", "virtual_cube_matrix_assemble",
+           "virtual_cube_matrix_gather", "virtual_cube_matrix_reduce_scatter", "cube3d_matmul_workspace_bytes",
+           "cube3d_matmul_blocks", "cube3d_status_string", "cube3d_version")
 
 
 def status_string(status: int) -> str:
@@ -215,3 +253,38 @@ def virtual_cube_linear_bwd_dw(desc, X_shards, dY_shards, dW_shards, stream=None
     _check(load().virtual_cube_linear_bwd_dw(ctypes.byref(desc), _ptr(X_shards), _ptr(dY_shards), _ptr(dW_shards),
                                              _stream(stream)), "virtual_cube_linear_bwd_dw")
     return dW_shards
+
+
+def virtual_cube_matrix_scatter(m, full, pieces, stream=None):
+    _check(load().virtual_cube_matrix_scatter(ctypes.byref(m), _ptr(full), _ptr(pieces), _stream(stream)),
+           "virtual_cube_matrix_scatter")
+    return pieces
+
+
+def virtual_cube_matrix_assemble(m, pieces, full, stream=None):
+    _check(load().virtual_cube_matrix_assemble(ctypes.byref(m), _ptr(pieces), _ptr(full), _stream(stream)),
+           "virtual_cube_matrix_assemble")
+    return full
+
+
+def virtual_cube_matrix_gather(m, pieces, blocks, stream=None):
+    _check(load().virtual_cube_matrix_gather(ctypes.byref(m), _ptr(pieces), _ptr(blocks), _stream(stream)),
+           "virtual_cube_matrix_gather")
+    return blocks
+
+
+def virtual_cube_matrix_reduce_scatter(m, partial_dtype, partials, pieces, stream=None):
+    _check(load().virtual_cube_matrix_reduce_scatter(ctypes.byref(m), partial_dtype, _ptr(partials), _ptr(pieces),
+                                                     _stream(stream)), "virtual_cube_matrix_reduce_scatter")
+    return pieces
+
+
+def cube3d_matmul_workspace_bytes(mm: Matmul) -> int:
+    return int(load().cube3d_matmul_workspace_bytes(ctypes.byref(mm)))
+
+
+def cube3d_matmul_blocks(mm, A_blocks, B_blocks, C_blocks, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().cube3d_matmul_blocks(ctypes.byref(mm), _ptr(A_blocks), _ptr(B_blocks), _ptr(C_blocks),
+                                       _ptr(workspace), ws_bytes, _stream(stream)), "cube3d_matmul_blocks")
+    return C_blocks

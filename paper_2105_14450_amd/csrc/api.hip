@@ -348,6 +348,140 @@ int virtual_cube_assemble(const cube3d_desc *desc, int which, const void *shards
     return storage_move(desc, which, false, shards, full, stream);
 }
 
+}  // extern "C"
+
+// ---- matrices placed anywhere on the cube; the three product forms (Algorithms 1-6) ----------------------
+namespace {
+
+int check_matrix(const cube3d_matrix *m, CubeGeom *g)
+{
+    if (!m) return CUBE3D_EINVAL;
+    if (m->q < 1) return CUBE3D_EINVAL;
+    if (m->row_axis < 0 || m->row_axis > 2 || m->col_axis < 0 || m->col_axis > 2 || m->row_axis == m->col_axis)
+        return CUBE3D_EINVAL;
+    if (m->split != CUBE3D_SPLIT_ROWS && m->split != CUBE3D_SPLIT_COLS) return CUBE3D_EINVAL;
+    if (m->q > 40) return CUBE3D_ESHAPE;
+    if (m->rows < 1 || m->cols < 1) return CUBE3D_ESHAPE;
+    const int64_t q = m->q, q2 = q * q;
+    const bool by_rows = m->split == CUBE3D_SPLIT_ROWS;
+    if (m->rows % (by_rows ? q2 : q) || m->cols % (by_rows ? q : q2)) return CUBE3D_ESHAPE;
+    if (elem_size(m->dtype) == 0) return CUBE3D_EDTYPE;
+    CubeGeom z{};
+    z.q = m->q;
+    z.p_ra = m->row_axis;
+    z.p_ca = m->col_axis;
+    z.p_sa = 3 - m->row_axis - m->col_axis;
+    z.p_split_rows = by_rows;
+    z.pR = m->rows; z.pC = m->cols;
+    z.pRb = m->rows / q; z.pCb = m->cols / q;
+    z.pRs = by_rows ? z.pRb / q : z.pRb;
+    z.pCs = by_rows ? z.pCb : z.pCb / q;
+    *g = z;
+    return CUBE3D_OK;
+}
+
+int matrix_move(const cube3d_matrix *m, int mode, const void *src, void *dst, void *stream)
+{
+    CubeGeom g;
+    int rc = check_matrix(m, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (!src || !dst || misaligned(src) || misaligned(dst)) return CUBE3D_EINVAL;
+    return cube_move(g, mode, elem_size(m->dtype), src, dst, static_cast<hipStream_t>(stream));
+}
+
+int build_matmul(const cube3d_matmul *mm, GemmArgs *out)
+{
+    if (!mm) return CUBE3D_EINVAL;
+    if (mm->q < 1) return CUBE3D_EINVAL;
+    if (mm->form != CUBE3D_FORM_AB && mm->form != CUBE3D_FORM_ABT && mm->form != CUBE3D_FORM_ATB) return CUBE3D_EINVAL;
+    if (mm->q > 40) return CUBE3D_ESHAPE;
+    if (mm->m < 1 || mm->n < 1 || mm->k < 1) return CUBE3D_ESHAPE;
+    if (elem_size(mm->in_dtype) == 0) return CUBE3D_EDTYPE;
+    if (mm->out_dtype != CUBE3D_F32 && mm->out_dtype != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    const bool fp8 = mm->in_dtype == CUBE3D_FP8_E4M3;
+    if (fp8)
+        for (float v : {mm->scale_a, mm->scale_b})
+            if (!(v > 0.f) || v > 3.0e38f) return CUBE3D_EINVAL;
+    GemmArgs a{};
+    a.batch = mm->q * mm->q * mm->q;
+    a.in_dtype = mm->in_dtype;
+    a.out_dtype = mm->out_dtype;
+    a.Mo = mm->m; a.No = mm->n; a.Kc = mm->k;
+    a.a_kmajor = mm->form != CUBE3D_FORM_ATB;     // A stored [m, k] unless the form transposes it
+    a.b_kmajor = mm->form == CUBE3D_FORM_ABT;     // B stored [n, k] only for A B^T
+    a.lda = a.a_kmajor ? mm->k : mm->m;
+    a.ldb = a.b_kmajor ? mm->k : mm->n;
+    a.ldc = mm->n;
+    a.alpha = fp8 ? mm->scale_a * mm->scale_b : 1.f;
+    a.strideA = mm->m * mm->k;
+    a.strideB = mm->n * mm->k;
+    a.strideC = mm->m * mm->n;
+    *out = a;
+    return CUBE3D_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int virtual_cube_matrix_scatter(const cube3d_matrix *m, const void *full, void *pieces, void *stream)
+{
+    return matrix_move(m, MV_PLACE_SCATTER, full, pieces, stream);
+}
+
+int virtual_cube_matrix_assemble(const cube3d_matrix *m, const void *pieces, void *full, void *stream)
+{
+    return matrix_move(m, MV_PLACE_ASSEMBLE, pieces, full, stream);
+}
+
+int virtual_cube_matrix_gather(const cube3d_matrix *m, const void *pieces, void *blocks, void *stream)
+{
+    return matrix_move(m, MV_PLACE_GATHER, pieces, blocks, stream);
+}
+
+int virtual_cube_matrix_reduce_scatter(const cube3d_matrix *m, int partial_dtype, const void *partials, void *pieces,
+                                       void *stream)
+{
+    CubeGeom g;
+    int rc = check_matrix(m, &g);
+    if (rc != CUBE3D_OK) return rc;
+    if (partial_dtype != CUBE3D_F32 && partial_dtype != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    if (m->dtype != CUBE3D_F32 && m->dtype != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    if (!partials || !pieces || misaligned(partials) || misaligned(pieces)) return CUBE3D_EINVAL;
+    return cube_reduce(g, MV_PLACE_REDUCE, partial_dtype, m->dtype, partials, pieces, nullptr,
+                       static_cast<hipStream_t>(stream));
+}
+
+size_t cube3d_matmul_workspace_bytes(const cube3d_matmul *mm)
+{
+    GemmArgs a;
+    if (build_matmul(mm, &a) != CUBE3D_OK) return 0;
+    return workspace_for(a);
+}
+
+int cube3d_matmul_blocks(const cube3d_matmul *mm, const void *A_blocks, const void *B_blocks, void *C_blocks,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    GemmArgs a;
+    int rc = build_matmul(mm, &a);
+    if (rc != CUBE3D_OK) return rc;
+    if (!A_blocks || !B_blocks || !C_blocks) return CUBE3D_EINVAL;
+    if (misaligned(A_blocks) || misaligned(B_blocks) || misaligned(C_blocks) || misaligned(workspace)) return CUBE3D_EINVAL;
+    a.A = A_blocks; a.B = B_blocks; a.C = C_blocks;
+    a.workspace = workspace;
+    a.workspace_bytes = workspace_bytes;
+    a.stream = static_cast<hipStream_t>(stream);
+    const size_t need = workspace_for(a);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return CUBE3D_EWORKSPACE;
+    rc = gemm_fast(a);
+    if (rc != CUBE3D_ENOTIMPL) return rc;
+    return gemm_generic(a);
+}
+
+}  // extern "C"
+
+extern "C" {
+
 const char *cube3d_status_string(int status)
 {
     switch (status) {

@@ -43,11 +43,52 @@ struct RowMap {
     int64_t dst, src, seg, seg_stride;
 };
 
+// A processor's indices along the three cube directions of a placement: block row, block column,
+// piece; and the distance in processor numbers between neighbours along the piece direction.
+struct PlaceCoords {
+    int rb, cb, s;
+    int64_t rstride;
+};
+
+__device__ __forceinline__ PlaceCoords decode_place(const CubeGeom &g, int r)
+{
+    const int idx[3] = {r / (g.q * g.q), (r / g.q) % g.q, r % g.q};
+    PlaceCoords c;
+    c.rb = g.p_ra == 0 ? idx[0] : g.p_ra == 1 ? idx[1] : idx[2];
+    c.cb = g.p_ca == 0 ? idx[0] : g.p_ca == 1 ? idx[1] : idx[2];
+    c.s = g.p_sa == 0 ? idx[0] : g.p_sa == 1 ? idx[1] : idx[2];
+    c.rstride = g.p_sa == 0 ? (int64_t)g.q * g.q : g.p_sa == 1 ? g.q : 1;
+    return c;
+}
+
 __device__ __forceinline__ RowMap map_copy_row(const CubeGeom &g, int mode, int r, int64_t row)
 {
-    const Coords c = decode_rank(g, r);
     RowMap m;
     m.seg_stride = 0;
+    if (mode >= MV_PLACE_GATHER) {
+        const PlaceCoords pc = decode_place(g, r);
+        if (mode == MV_PLACE_GATHER) {
+            m.dst = ((int64_t)r * g.pRb + row) * g.pCb;
+            if (g.p_split_rows) {   // row piece s' comes from the processor with piece index s'
+                const int64_t s2 = row / g.pRs, rr = row - s2 * g.pRs;
+                m.seg = g.pCb;
+                m.src = ((r + (s2 - pc.s) * pc.rstride) * g.pRs + rr) * g.pCb;
+            } else {                // every row is q column pieces, one per processor of the group
+                m.seg = g.pCs;
+                m.src = ((r - pc.s * pc.rstride) * g.pRb + row) * g.pCs;
+                m.seg_stride = pc.rstride * g.pRb * g.pCs;
+            }
+        } else {
+            m.seg = g.pCs;
+            const int64_t sh = ((int64_t)r * g.pRs + row) * g.pCs;
+            const int64_t fu = ((int64_t)pc.rb * g.pRb + (g.p_split_rows ? (int64_t)pc.s * g.pRs : 0) + row) * g.pC +
+                               (int64_t)pc.cb * g.pCb + (g.p_split_rows ? 0 : (int64_t)pc.s * g.pCs);
+            m.dst = mode == MV_PLACE_SCATTER ? sh : fu;
+            m.src = mode == MV_PLACE_SCATTER ? fu : sh;
+        }
+        return m;
+    }
+    const Coords c = decode_rank(g, r);
     switch (mode) {
     case MV_GATHER_X: {  // dst [Mb,Kb]; row panel a' comes from processor (i, a', b)
         const int64_t a2 = row / g.Ms, rr = row - a2 * g.Ms;
@@ -191,12 +232,19 @@ __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, 
         seg = g.Kb; dst_ld = g.Kb; src_ld = g.Kb; src_row0 = (int64_t)c.a * g.Ms; src_col0 = 0;
         src0 = rank_index(g, c.i, 0, c.b) * g.Mb * g.Kb;
         src_step = (rank_index(g, c.i, 1 % g.q, c.b) - rank_index(g, c.i, 0, c.b)) * g.Mb * g.Kb;
-    } else {  // MV_REDUCE_DW: keep column panel i of the sum over i'
+    } else if (mode == MV_REDUCE_DW) {  // keep column panel i of the sum over i'
         seg = g.Ns; dst_ld = g.Ns; src_ld = g.Nb; src_row0 = 0; src_col0 = (int64_t)c.i * g.Ns;
         src0 = rank_index(g, 0, c.a, c.b) * g.Kb * g.Nb;
         src_step = (rank_index(g, 1 % g.q, c.a, c.b) - rank_index(g, 0, c.a, c.b)) * g.Kb * g.Nb;
+    } else {  // MV_PLACE_REDUCE: keep piece s of the sum over the processors of the piece direction
+        const PlaceCoords pc = decode_place(g, r);
+        seg = g.pCs; dst_ld = g.pCs; src_ld = g.pCb;
+        src_row0 = g.p_split_rows ? (int64_t)pc.s * g.pRs : 0;
+        src_col0 = g.p_split_rows ? 0 : (int64_t)pc.s * g.pCs;
+        src0 = (r - pc.s * pc.rstride) * g.pRb * g.pCb;
+        src_step = pc.rstride * g.pRb * g.pCb;
     }
-    const int64_t dst_rows = mode == MV_REDUCE_DW ? g.Kb : g.Ms;
+    const int64_t dst_rows = mode == MV_PLACE_REDUCE ? g.pRs : mode == MV_REDUCE_DW ? g.Kb : g.Ms;
     const int q = g.q;
 
     for (int w = 0; w < RPW; ++w) {
@@ -261,6 +309,9 @@ int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, h
     case MV_SCATTER_X: case MV_ASSEMBLE_X: rows = g.Ms; seg = g.Kb; break;
     case MV_SCATTER_W: case MV_ASSEMBLE_W: rows = g.Kb; seg = g.Ns; break;
     case MV_SCATTER_Y: case MV_ASSEMBLE_Y: rows = g.Ms; seg = g.Nb; break;
+    case MV_PLACE_GATHER:
+        rows = g.pRb; seg = g.p_split_rows ? g.pCb : g.pCs; nseg = g.p_split_rows ? 1 : g.q; break;
+    case MV_PLACE_SCATTER: case MV_PLACE_ASSEMBLE: rows = g.pRs; seg = g.pCs; break;
     default: return CUBE3D_EINVAL;
     }
     const int64_t nblk = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
@@ -291,6 +342,7 @@ int cube_reduce(const CubeGeom &g, int mode, int partial_dtype, int shard_dtype,
     case MV_REDUCE_Y: rows = g.Ms; seg = g.Nb; break;
     case MV_REDUCE_DX: rows = g.Ms; seg = g.Kb; break;
     case MV_REDUCE_DW: rows = g.Kb; seg = g.Ns; break;
+    case MV_PLACE_REDUCE: rows = g.pRs; seg = g.pCs; break;
     default: return CUBE3D_EINVAL;
     }
     if (g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;

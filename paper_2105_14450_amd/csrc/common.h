@@ -82,6 +82,12 @@ struct CubeGeom {
     int q;
     int in_axis_z;  // 0: input gathered along y, output reduced along z; 1: exchanged
     int64_t M, K, N, Mb, Kb, Nb, Ms, Ns;
+    // MV_PLACE_* modes only: placement of one [pR, pC] matrix (Section 3.1.1 generalised to the
+    // operands of Algorithms 3-6).  Cube directions 0 / 1 / 2 = x / y / z: the index along p_ra picks
+    // the block row, along p_ca the block column; along p_sa a [pRb, pCb] block is cut once more into
+    // q pieces [pRs, pCs], by rows (p_split_rows) or by columns.
+    int p_ra, p_ca, p_sa, p_split_rows;
+    int64_t pR, pC, pRb, pCb, pRs, pCs;
 };
 
 enum MoveMode {
@@ -99,7 +105,11 @@ enum MoveMode {
     MV_REDUCE_DW,
     MV_SCATTER_BIAS,   // full vector -> diagonal storage
     MV_ASSEMBLE_BIAS,  // diagonal storage -> full vector
-    MV_GATHER_BIAS     // diagonal storage -> one [Nb] block per processor
+    MV_GATHER_BIAS,    // diagonal storage -> one [Nb] block per processor
+    MV_PLACE_GATHER,   // any placement: shards -> one whole block per processor (all-gather along p_sa)
+    MV_PLACE_SCATTER,  // full matrix -> shards
+    MV_PLACE_ASSEMBLE, // shards -> full matrix
+    MV_PLACE_REDUCE    // partial blocks -> shards (reduce-scatter along p_sa)
 };
 
 int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, hipStream_t stream);

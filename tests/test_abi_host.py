@@ -153,6 +153,56 @@ def test_cube_linear_argument_errors(lib):
         assert g(ctypes.byref(good(N=6)), FAKE, FAKE, FAKE, None) == c3.ESHAPE
 
 
+def test_matrix_and_matmul_argument_errors(lib):
+    def mat(**kw):
+        a = dict(q=2, rows=16, cols=8, row_axis=c3.AXIS_X, col_axis=c3.AXIS_Z, split=c3.SPLIT_ROWS, dtype=c3.F32)
+        a.update(kw)
+        return c3.make_matrix(**a)
+
+    moves = (lib.virtual_cube_matrix_scatter, lib.virtual_cube_matrix_assemble, lib.virtual_cube_matrix_gather)
+    for f in moves:
+        assert f(None, FAKE, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(mat()), None, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(mat()), FAKE, ODD, None) == c3.EINVAL
+        assert f(ctypes.byref(mat(q=0)), FAKE, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(mat(col_axis=c3.AXIS_X)), FAKE, FAKE, None) == c3.EINVAL   # same direction twice
+        assert f(ctypes.byref(mat(row_axis=3)), FAKE, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(mat(split=2)), FAKE, FAKE, None) == c3.EINVAL
+        assert f(ctypes.byref(mat(rows=18)), FAKE, FAKE, None) == c3.ESHAPE              # q^2 does not divide rows
+        assert f(ctypes.byref(mat(cols=7)), FAKE, FAKE, None) == c3.ESHAPE
+        assert f(ctypes.byref(mat(split=c3.SPLIT_COLS, cols=6)), FAKE, FAKE, None) == c3.ESHAPE
+        assert f(ctypes.byref(mat(dtype=9)), FAKE, FAKE, None) == c3.EDTYPE
+    rs = lib.virtual_cube_matrix_reduce_scatter
+    assert rs(None, c3.F32, FAKE, FAKE, None) == c3.EINVAL
+    assert rs(ctypes.byref(mat()), c3.FP8_E4M3, FAKE, FAKE, None) == c3.EDTYPE
+    assert rs(ctypes.byref(mat(dtype=c3.FP8_E4M3)), c3.F32, FAKE, FAKE, None) == c3.EDTYPE
+    assert rs(ctypes.byref(mat()), c3.F32, None, FAKE, None) == c3.EINVAL
+    assert rs(ctypes.byref(mat(rows=6)), c3.F32, FAKE, FAKE, None) == c3.ESHAPE
+
+    def mm(**kw):
+        a = dict(q=2, form=c3.FORM_ABT, m=64, n=64, k=64, in_dtype=c3.F32, out_dtype=c3.F32)
+        a.update(kw)
+        return c3.make_matmul(**a)
+
+    f = lib.cube3d_matmul_blocks
+    assert f(None, FAKE, FAKE, FAKE, None, 0, None) == c3.EINVAL
+    assert f(ctypes.byref(mm(form=3)), FAKE, FAKE, FAKE, None, 0, None) == c3.EINVAL
+    assert f(ctypes.byref(mm(q=0)), FAKE, FAKE, FAKE, None, 0, None) == c3.EINVAL
+    assert f(ctypes.byref(mm(k=0)), FAKE, FAKE, FAKE, None, 0, None) == c3.ESHAPE
+    assert f(ctypes.byref(mm(in_dtype=5)), FAKE, FAKE, FAKE, None, 0, None) == c3.EDTYPE
+    assert f(ctypes.byref(mm(out_dtype=c3.FP8_E4M3)), FAKE, FAKE, FAKE, None, 0, None) == c3.EDTYPE
+    assert f(ctypes.byref(mm(in_dtype=c3.FP8_E4M3, scale_a=0.0)), FAKE, FAKE, FAKE, None, 0, None) == c3.EINVAL
+    assert f(ctypes.byref(mm()), None, FAKE, FAKE, None, 0, None) == c3.EINVAL
+    assert f(ctypes.byref(mm()), FAKE, FAKE, ODD, None, 0, None) == c3.EINVAL
+    assert c3.cube3d_matmul_workspace_bytes(mm(form=7)) == 0
+    # one 128 x 128 block per processor with a long contraction: split-K needs a workspace
+    deep = mm(q=1, m=128, n=128, k=8192, in_dtype=c3.BF16, out_dtype=c3.BF16)
+    need = c3.cube3d_matmul_workspace_bytes(deep)
+    assert need > 0
+    assert f(ctypes.byref(deep), FAKE, FAKE, FAKE, None, 0, None) == c3.EWORKSPACE
+    assert f(ctypes.byref(deep), FAKE, FAKE, FAKE, FAKE, need - 1, None) == c3.EWORKSPACE
+
+
 def test_workspace_query_and_strings(lib):
     assert c3.cube3d_workspace_bytes(good(M=7), c3.OP_FWD, False) == 0
     assert c3.cube3d_workspace_bytes(good(), 42, False) == 0
