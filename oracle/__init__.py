@@ -13,6 +13,8 @@ layout    the load-balanced storage of Section 3.1.1 and the all-gather /
 dist3d    the three matrix-product forms of Section 3.1.2 on the cube, forward and
           backward (Algorithms 1-6), for any placement of the matrices, as numpy
           slicing around the triple loops of ``matmul``
+mlp       the MLP block of Section 3.2 (two linear layers around an element-wise
+          activation) and its backward pass, as full-matrix fp64 arithmetic
 numfmt    decoding of bf16 / fp8-e4m3 bit patterns to fp64 and the single
           round-to-nearest-even of an fp64 result to the compared dtype
 """
