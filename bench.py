@@ -222,6 +222,10 @@ def main():
             extra["config3"] = bench_virtual_cube(c3, synth, torch, np, timed)
         except Exception as exc:
             extra["config3"] = {"error": repr(exc)}
+        try:
+            extra["config3"]["layer_chain"] = bench_layer_chain(c3, torch, stream)
+        except Exception as exc:
+            extra["config3"]["layer_chain"] = {"error": repr(exc)}
         out["per_config"] = extra
 
     # ---- the oracle on the host cores, bounded sample -------------------------------------------------
@@ -342,6 +346,83 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
     res["cube_products_tflops"] = round(cube_flop / (cube_ms * 1e-3) / 1e12, 1)
     res["cube_frac_of_bf16_peak"] = round(res["cube_products_tflops"] / PEAK_TFLOPS["bf16"], 4)
     return res
+
+
+def bench_layer_chain(c3, torch, stream):
+    """The four linears of config 3 as one chained layer step on the 64-processor virtual cube, forward and
+    backward, in-place cube products with bias, the direction exchange between consecutive linears
+    (y, z, y, z) and the activation between the two MLP linears: timed eagerly and as one captured graph."""
+    q, M = 4, 8192
+    n = q ** 3
+    i16, f32 = torch.int16, torch.float32
+    g = torch.Generator(device="cuda").manual_seed(33)
+    mk = lambda shape, s: (torch.randn(shape, device="cuda", generator=g) * s).to(torch.bfloat16).view(i16)
+    new = lambda shape, dt=i16: torch.empty(shape, dtype=dt, device="cuda")
+    L = {}
+    flop = 0.0
+    for name, K, N, ax in CONFIG3:
+        d = c3.make_desc(q, M, K, N, in_dtype=c3.BF16, out_dtype=c3.F32, shard_dtype=c3.BF16,
+                         in_axis=c3.AXIS_Y if ax == "y" else c3.AXIS_Z)
+        Kb, Nb, Ms, Ns = K // q, N // q, M // q ** 2, N // q ** 2
+        L[name] = dict(d=d, x=mk((n, Ms, Kb), 1.0), w=mk((n, Kb, Ns), 0.02), b=torch.randn((n, Ns), device="cuda", generator=g),
+                       y=new((n, Ms, Nb)), dy=mk((n, Ms, Nb), 1.0), dx=new((n, Ms, Kb)), dw=new((n, Kb, Ns)),
+                       db=new((n, Ns), f32),
+                       ws=new((c3.cube3d_workspace_bytes(d, c3.OP_BIAS_BWD, True),), torch.uint8))
+        flop += 3 * 2.0 * M * K * N
+    up, down = L["mlp_up"], L["mlp_down"]
+    down["x"] = new(tuple(up["y"].shape))      # H = act(Z): the up-projection's output shards, as stored, are its input
+    dz = new(tuple(up["y"].shape))
+
+    def fwd(l):
+        c3.virtual_cube_linear_fwd(l["d"], l["x"], l["w"], l["b"], l["y"])
+
+    def bwd(l, dy):
+        c3.virtual_cube_linear_bwd_dx(l["d"], dy, l["w"], l["dx"])
+        c3.virtual_cube_linear_bwd_dw(l["d"], l["x"], dy, l["dw"])
+        c3.virtual_cube_bias_bwd(l["d"], dy, l["db"], l["ws"])
+
+    def step():
+        fwd(L["qkv"])
+        fwd(L["attn_out"])
+        fwd(up)
+        c3.cube3d_activation_fwd(c3.ACT_GELU, c3.BF16, c3.BF16, up["y"], down["x"])
+        fwd(down)
+        bwd(down, down["dy"])
+        c3.cube3d_activation_bwd(c3.ACT_GELU, c3.BF16, c3.BF16, c3.BF16, up["y"], down["dx"], dz)
+        bwd(up, dz)
+        bwd(L["attn_out"], L["attn_out"]["dy"])
+        bwd(L["qkv"], L["qkv"]["dy"])
+
+    def timed(run, iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(iters):
+            run()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    step()
+    step()
+    eager_ms = timed(step, 10)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    graph.replay()
+    graph_ms = timed(graph.replay, 10)
+    act_n = up["y"].numel()
+    act_ms = timed(lambda: c3.cube3d_activation_fwd(c3.ACT_GELU, c3.BF16, c3.BF16, up["y"], down["x"]), 10)
+    actb_ms = timed(lambda: c3.cube3d_activation_bwd(c3.ACT_GELU, c3.BF16, c3.BF16, c3.BF16, up["y"], down["dx"], dz), 10)
+    return {"what": "qkv, attn-out, MLP-up, GELU, MLP-down forward, then the backward of all four: in-place cube "
+                    "products with bias, bf16, M = 8192 tokens, q = 4 (26 kernel launches)",
+            "flop": flop, "eager_ms": round(eager_ms, 3), "graph_ms": round(graph_ms, 3),
+            "tflops_graph": round(flop / (graph_ms * 1e-3) / 1e12, 1),
+            "frac_of_bf16_peak": round(flop / (graph_ms * 1e-3) / 1e12 / PEAK_TFLOPS["bf16"], 4),
+            "activation_fwd": {"avg_us": round(act_ms * 1e3, 1), "GBps": round(act_n * 4 / (act_ms * 1e-3) / 1e9, 1)},
+            "activation_bwd": {"avg_us": round(actb_ms * 1e3, 1), "GBps": round(act_n * 6 / (actb_ms * 1e-3) / 1e9, 1)}}
 
 
 def cpu_baseline(host, dt, seconds):

@@ -340,6 +340,29 @@ size_t cube3d_matmul_workspace_bytes(const cube3d_matmul *mm);
 int cube3d_matmul_blocks(const cube3d_matmul *mm, const void *A_blocks, const void *B_blocks, void *C_blocks,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The activation between the two 3-D linear layers of the MLP block (Section 3.2): it acts
+ * element by element, so every processor applies it to its own shard and no data moves; here
+ * one call covers any array of n elements (a whole cube buffer).  The output of a layer that
+ * gathers its input in y is, as stored, the input of a layer that gathers in z (Section 3.1.1,
+ * last paragraph), so the chain is: linear (in_axis = y) -> activation -> linear (in_axis = z).
+ *   cube3d_activation_fwd:  h = act(z)
+ *   cube3d_activation_bwd:  dz = dh * act'(z)
+ * kind: CUBE3D_ACT_RELU = max(z, 0), slope 0 at 0; CUBE3D_ACT_GELU = z * Phi(z), Phi the standard
+ * normal distribution function (erf form), evaluated in fp32.  (The paper does not name the
+ * activation.)  Every dtype is CUBE3D_F32 or CUBE3D_BF16, results rounded once to nearest even;
+ * n >= 0; pointers 16-byte aligned; z / dh and the output may not overlap partially (in place,
+ * with equal dtypes, is allowed).
+ */
+typedef enum cube3d_activation {
+    CUBE3D_ACT_RELU = 0,
+    CUBE3D_ACT_GELU = 1
+} cube3d_activation;
+
+int cube3d_activation_fwd(int kind, int z_dtype, int h_dtype, int64_t n, const void *z, void *h, void *stream);
+int cube3d_activation_bwd(int kind, int z_dtype, int dh_dtype, int dz_dtype, int64_t n, const void *z, const void *dh,
+                          void *dz, void *stream);
+
 const char *cube3d_status_string(int status);
 int cube3d_version(void);
 

@@ -18,6 +18,7 @@ OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW, OPERAND_BIA
 OP_FWD, OP_BWD_DX, OP_BWD_DW, OP_BIAS_BWD = 0, 1, 2, 3
 SPLIT_ROWS, SPLIT_COLS = 0, 1
 FORM_AB, FORM_ABT, FORM_ATB = 0, 1, 2
+ACT_RELU, ACT_GELU = 0, 1
 ALL_RANKS = (-1, -1, -1)
 
 DTYPE_CODES = {"f32": F32, "bf16": BF16, "fp8_e4m3": FP8_E4M3}
@@ -124,6 +125,10 @@ def load():
     lib.cube3d_matmul_workspace_bytes.restype = sz
     lib.cube3d_matmul_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.cube3d_matmul_blocks.restype = ci
+    lib.cube3d_activation_fwd.argtypes = [ci, ci, ci, ctypes.c_int64, vp, vp, vp]
+    lib.cube3d_activation_fwd.restype = ci
+    lib.cube3d_activation_bwd.argtypes = [ci, ci, ci, ci, ctypes.c_int64, vp, vp, vp, vp]
+    lib.cube3d_activation_bwd.restype = ci
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
     lib.cube3d_version.restype = ci
@@ -137,7 +142,8 @@ EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", 
            "virtual_cube_bias_bwd", "virtual_cube_linear_fwd", "virtual_cube_linear_bwd_dx",
            "virtual_cube_linear_bwd_dw", "virtual_cube_matrix_scatter", "virtual_cube_matrix_assemble",
            "virtual_cube_matrix_gather", "virtual_cube_matrix_reduce_scatter", "cube3d_matmul_workspace_bytes",
-           "cube3d_matmul_blocks", "cube3d_status_string", "cube3d_version")
+           "cube3d_matmul_blocks", "cube3d_activation_fwd", "cube3d_activation_bwd", "cube3d_status_string",
+           "cube3d_version")
 
 
 def status_string(status: int) -> str:
@@ -288,3 +294,15 @@ def cube3d_matmul_blocks(mm, A_blocks, B_blocks, C_blocks, workspace=None, strea
     _check(load().cube3d_matmul_blocks(ctypes.byref(mm), _ptr(A_blocks), _ptr(B_blocks), _ptr(C_blocks),
                                        _ptr(workspace), ws_bytes, _stream(stream)), "cube3d_matmul_blocks")
     return C_blocks
+
+
+def cube3d_activation_fwd(kind, z_dtype, h_dtype, z, h, stream=None):
+    _check(load().cube3d_activation_fwd(kind, z_dtype, h_dtype, z.numel(), _ptr(z), _ptr(h), _stream(stream)),
+           "cube3d_activation_fwd")
+    return h
+
+
+def cube3d_activation_bwd(kind, z_dtype, dh_dtype, dz_dtype, z, dh, dz, stream=None):
+    _check(load().cube3d_activation_bwd(kind, z_dtype, dh_dtype, dz_dtype, z.numel(), _ptr(z), _ptr(dh), _ptr(dz),
+                                        _stream(stream)), "cube3d_activation_bwd")
+    return dz

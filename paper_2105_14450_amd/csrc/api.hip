@@ -482,6 +482,29 @@ int cube3d_matmul_blocks(const cube3d_matmul *mm, const void *A_blocks, const vo
 
 extern "C" {
 
+int cube3d_activation_fwd(int kind, int z_dtype, int h_dtype, int64_t n, const void *z, void *h, void *stream)
+{
+    if (kind != CUBE3D_ACT_RELU && kind != CUBE3D_ACT_GELU) return CUBE3D_EINVAL;
+    if (n < 0) return CUBE3D_ESHAPE;
+    for (int t : {z_dtype, h_dtype})
+        if (t != CUBE3D_F32 && t != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    if (!z || !h || misaligned(z) || misaligned(h)) return CUBE3D_EINVAL;
+    if (n == 0) return CUBE3D_OK;
+    return activation_fwd(kind, z_dtype, h_dtype, n, z, h, static_cast<hipStream_t>(stream));
+}
+
+int cube3d_activation_bwd(int kind, int z_dtype, int dh_dtype, int dz_dtype, int64_t n, const void *z, const void *dh,
+                          void *dz, void *stream)
+{
+    if (kind != CUBE3D_ACT_RELU && kind != CUBE3D_ACT_GELU) return CUBE3D_EINVAL;
+    if (n < 0) return CUBE3D_ESHAPE;
+    for (int t : {z_dtype, dh_dtype, dz_dtype})
+        if (t != CUBE3D_F32 && t != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    if (!z || !dh || !dz || misaligned(z) || misaligned(dh) || misaligned(dz)) return CUBE3D_EINVAL;
+    if (n == 0) return CUBE3D_OK;
+    return activation_bwd(kind, z_dtype, dh_dtype, dz_dtype, n, z, dh, dz, static_cast<hipStream_t>(stream));
+}
+
 const char *cube3d_status_string(int status)
 {
     switch (status) {

@@ -122,6 +122,11 @@ size_t cube_bias_bwd_workspace(const CubeGeom &g, int dy_dtype);
 int cube_bias_bwd(const CubeGeom &g, int dy_dtype, float scale_dy, const void *dy_shards, float *dbias_diag,
                   void *workspace, size_t workspace_bytes, hipStream_t stream);
 
+// Element-wise activation over n elements (dtypes F32 or BF16 already checked by the caller).
+int activation_fwd(int kind, int z_dtype, int h_dtype, int64_t n, const void *z, void *h, hipStream_t stream);
+int activation_bwd(int kind, int z_dtype, int g_dtype, int dz_dtype, int64_t n, const void *z, const void *dh, void *dz,
+                   hipStream_t stream);
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? CUBE3D_OK : CUBE3D_ELAUNCH;

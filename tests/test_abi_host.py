@@ -203,6 +203,22 @@ def test_matrix_and_matmul_argument_errors(lib):
     assert f(ctypes.byref(deep), FAKE, FAKE, FAKE, FAKE, need - 1, None) == c3.EWORKSPACE
 
 
+def test_activation_argument_errors(lib):
+    f, b = lib.cube3d_activation_fwd, lib.cube3d_activation_bwd
+    assert f(2, c3.F32, c3.F32, 64, FAKE, FAKE, None) == c3.EINVAL
+    assert f(c3.ACT_GELU, c3.FP8_E4M3, c3.F32, 64, FAKE, FAKE, None) == c3.EDTYPE
+    assert f(c3.ACT_GELU, c3.F32, 7, 64, FAKE, FAKE, None) == c3.EDTYPE
+    assert f(c3.ACT_RELU, c3.F32, c3.F32, -1, FAKE, FAKE, None) == c3.ESHAPE
+    assert f(c3.ACT_RELU, c3.F32, c3.F32, 64, None, FAKE, None) == c3.EINVAL
+    assert f(c3.ACT_RELU, c3.F32, c3.F32, 64, FAKE, ODD, None) == c3.EINVAL
+    assert f(c3.ACT_RELU, c3.F32, c3.BF16, 0, FAKE, FAKE, None) == c3.OK          # nothing to do, nothing launched
+    assert b(-1, c3.F32, c3.F32, c3.F32, 64, FAKE, FAKE, FAKE, None) == c3.EINVAL
+    assert b(c3.ACT_GELU, c3.F32, c3.FP8_E4M3, c3.F32, 64, FAKE, FAKE, FAKE, None) == c3.EDTYPE
+    assert b(c3.ACT_GELU, c3.F32, c3.F32, c3.F32, 64, FAKE, None, FAKE, None) == c3.EINVAL
+    assert b(c3.ACT_GELU, c3.F32, c3.F32, c3.F32, 64, FAKE, FAKE, ODD, None) == c3.EINVAL
+    assert b(c3.ACT_GELU, c3.BF16, c3.BF16, c3.BF16, 0, FAKE, FAKE, FAKE, None) == c3.OK
+
+
 def test_workspace_query_and_strings(lib):
     assert c3.cube3d_workspace_bytes(good(M=7), c3.OP_FWD, False) == 0
     assert c3.cube3d_workspace_bytes(good(), 42, False) == 0

@@ -1,0 +1,182 @@
+"""GPU parity of the MLP block (Section 3.2): two 3-D linear layers around an element-wise
+activation, forward and backward, with the direction exchange between them; and the same chain
+captured in a HIP graph.  Every step runs through the C ABI; the reference is the oracle's
+full-matrix arithmetic with the same storage roundings.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2105_14450_amd as c3
+from oracle import mlp, numfmt
+from oracle.layout import Cube
+from paper_2105_14450_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+KIND = {"relu": c3.ACT_RELU, "gelu": c3.ACT_GELU}
+TID_B1, TID_B2, TID_W2 = 11, 12, 13
+
+
+def _round(dtype):
+    return (lambda x: numfmt.round_to(x, dtype)) if dtype == "bf16" else (lambda x: x.astype(np.float32).astype(np.float64))
+
+
+@pytest.mark.parametrize("kind", ["relu", "gelu"])
+@pytest.mark.parametrize("zt,ht", [("f32", "f32"), ("bf16", "bf16"), ("f32", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("n", [0, 5, 4096, 1000003])
+def test_activation(kind, zt, ht, n):
+    z_raw, _ = synth.store(synth.draw((n,), "normal", 81, 1, 2.0), zt)
+    g_raw, _ = synth.store(synth.draw((n,), "normal", 81, 2), ht)
+    z, g = numfmt.decode(z_raw, zt), numfmt.decode(g_raw, ht)
+    zd, gd = gu.to_device(z_raw) if n else gu.empty((16,), zt), gu.to_device(g_raw) if n else gu.empty((16,), ht)
+    h, dz = gu.empty((max(n, 16),), ht), gu.empty((max(n, 16),), ht)
+    load = c3.binding.load()
+    import ctypes
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert load.cube3d_activation_fwd(KIND[kind], gu.CODE[zt], gu.CODE[ht], n, zd.data_ptr(), h.data_ptr(), s) == 0
+    assert load.cube3d_activation_bwd(KIND[kind], gu.CODE[zt], gu.CODE[ht], gu.CODE[ht], n, zd.data_ptr(), gd.data_ptr(),
+                                      dz.data_ptr(), s) == 0
+    torch.cuda.synchronize()
+    got_h, got_dz = gu.to_host(h, ht)[:n], gu.to_host(dz, ht)[:n]
+    ref_h, ref_dz = mlp.act(z, kind), g * mlp.act_grad(z, kind)
+    if kind == "relu":      # exact: a copy or a zero, one rounding
+        np.testing.assert_array_equal(got_h, _round(ht)(ref_h))
+        np.testing.assert_array_equal(got_dz, _round(ht)(ref_dz))
+    else:                   # fp32 erf / exp, then one rounding to the stored type
+        eps = 2.0 ** -8 if ht == "bf16" else 4e-6
+        assert np.all(np.abs(got_h - ref_h) <= eps * np.abs(ref_h) + 1e-6)
+        assert np.all(np.abs(got_dz - ref_dz) <= eps * np.abs(ref_dz) + 1e-6)
+    # untouched beyond n
+    if n:
+        assert np.all(gu.raw_host(h)[n:].view(np.uint8) == 0xFF)
+
+
+class Block:
+    """Device buffers and descriptors of one MLP block on the q^3 cube (in-place cube products)."""
+
+    def __init__(self, q, M, K, N1, N2, dtype, dist, seed, kind):
+        self.q, self.M, self.K, self.N1, self.N2, self.dtype, self.kind = q, M, K, N1, N2, dtype, kind
+        integer = dist == "int"
+        sig = 0.02 if dist == "normal" else 1.0
+        sw2 = sig if not integer else 1.0
+        self.raw = {
+            "X": synth.store(synth.draw((M, K), dist, seed, synth.TID_X), dtype, integer)[0],
+            "W1": synth.store(synth.draw((K, N1), dist, seed, synth.TID_W, sig), dtype, integer)[0],
+            "W2": synth.store(synth.draw((N1, N2), dist, seed, TID_W2, sw2), dtype, integer)[0],
+            "dY": synth.store(synth.draw((M, N2), dist, seed, synth.TID_DY), dtype, integer)[0],
+        }
+        self.b1 = synth.draw((N1,), "int" if integer else "uniform", seed, TID_B1).astype(np.float32)
+        self.b2 = synth.draw((N2,), "int" if integer else "uniform", seed, TID_B2).astype(np.float32)
+        self.val = {k: numfmt.decode(v, dtype) for k, v in self.raw.items()}
+        code = gu.CODE[dtype]
+        # layer 1 gathers its input in y and leaves its output in z; layer 2 takes it there
+        self.d1 = c3.make_desc(q, M, K, N1, in_dtype=code, out_dtype=c3.F32, shard_dtype=code, in_axis=c3.AXIS_Y)
+        self.d2 = c3.make_desc(q, M, N1, N2, in_dtype=code, out_dtype=c3.F32, shard_dtype=code, in_axis=c3.AXIS_Z)
+        self.c1, self.c2 = Cube(q, M, K, N1, "y"), Cube(q, M, N1, N2, "z")
+        n, c1, c2, e = q ** 3, self.c1, self.c2, gu.empty
+        self.x, self.w1 = e((n, c1.Ms, c1.Kb), dtype), e((n, c1.Kb, c1.Ns), dtype)
+        self.w2, self.dy = e((n, c2.Kb, c2.Ns), dtype), e((n, c2.Ms, c2.Nb), dtype)
+        self.b1d, self.b2d = e((n, c1.Ns), "f32"), e((n, c2.Ns), "f32")
+        c3.virtual_cube_scatter(self.d1, c3.OPERAND_X, gu.to_device(self.raw["X"]), self.x)
+        c3.virtual_cube_scatter(self.d1, c3.OPERAND_W, gu.to_device(self.raw["W1"]), self.w1)
+        c3.virtual_cube_scatter(self.d2, c3.OPERAND_W, gu.to_device(self.raw["W2"]), self.w2)
+        c3.virtual_cube_scatter(self.d2, c3.OPERAND_DY, gu.to_device(self.raw["dY"]), self.dy)
+        c3.virtual_cube_scatter(self.d1, c3.OPERAND_BIAS, gu.to_device(self.b1), self.b1d)
+        c3.virtual_cube_scatter(self.d2, c3.OPERAND_BIAS, gu.to_device(self.b2), self.b2d)
+        # results and intermediates (all pieces of the cube, as every processor would hold them)
+        self.z, self.h = e((n, c1.Ms, c1.Nb), dtype), e((n, c1.Ms, c1.Nb), dtype)
+        self.y = e((n, c2.Ms, c2.Nb), dtype)
+        self.dh, self.dz = e((n, c2.Ms, c2.Kb), dtype), e((n, c1.Ms, c1.Nb), dtype)
+        self.dx, self.dw1 = e((n, c1.Ms, c1.Kb), dtype), e((n, c1.Kb, c1.Ns), dtype)
+        self.dw2 = e((n, c2.Kb, c2.Ns), dtype)
+        self.db1, self.db2 = e((n, c1.Ns), "f32"), e((n, c2.Ns), "f32")
+        self.ws1 = gu.workspace(self.d1, c3.OP_BIAS_BWD, True)
+        self.ws2 = gu.workspace(self.d2, c3.OP_BIAS_BWD, True)
+
+    def step(self):
+        """Forward and backward of the block: eleven launches' worth of library calls on the current stream."""
+        code, k = gu.CODE[self.dtype], KIND[self.kind]
+        c3.virtual_cube_linear_fwd(self.d1, self.x, self.w1, self.b1d, self.z)
+        c3.cube3d_activation_fwd(k, code, code, self.z, self.h)
+        c3.virtual_cube_linear_fwd(self.d2, self.h, self.w2, self.b2d, self.y)       # input taken in z, as stored
+        c3.virtual_cube_linear_bwd_dx(self.d2, self.dy, self.w2, self.dh)
+        c3.virtual_cube_linear_bwd_dw(self.d2, self.h, self.dy, self.dw2)
+        c3.virtual_cube_bias_bwd(self.d2, self.dy, self.db2, self.ws2)
+        c3.cube3d_activation_bwd(k, code, code, code, self.z, self.dh, self.dz)
+        c3.virtual_cube_linear_bwd_dx(self.d1, self.dz, self.w1, self.dx)
+        c3.virtual_cube_linear_bwd_dw(self.d1, self.x, self.dz, self.dw1)
+        c3.virtual_cube_bias_bwd(self.d1, self.dz, self.db1, self.ws1)
+
+    def results(self):
+        """Assembled full matrices / vectors as fp64."""
+        d1, d2, dt, e = self.d1, self.d2, self.dtype, gu.empty
+        out = {}
+        for name, desc, which, pieces, shape, t in (
+                ("Z", d1, c3.OPERAND_Y, self.z, (self.M, self.N1), dt), ("H", d2, c3.OPERAND_X, self.h, (self.M, self.N1), dt),
+                ("Y", d2, c3.OPERAND_Y, self.y, (self.M, self.N2), dt), ("dH", d2, c3.OPERAND_DX, self.dh, (self.M, self.N1), dt),
+                ("dZ", d1, c3.OPERAND_DY, self.dz, (self.M, self.N1), dt), ("dX", d1, c3.OPERAND_DX, self.dx, (self.M, self.K), dt),
+                ("dW1", d1, c3.OPERAND_DW, self.dw1, (self.K, self.N1), dt), ("dW2", d2, c3.OPERAND_DW, self.dw2, (self.N1, self.N2), dt),
+                ("db1", d1, c3.OPERAND_BIAS, self.db1, (self.N1,), "f32"), ("db2", d2, c3.OPERAND_BIAS, self.db2, (self.N2,), "f32")):
+            full = e(shape, t)
+            c3.virtual_cube_assemble(desc, which, pieces, full)
+            out[name] = full
+        torch.cuda.synchronize()
+        return {k: gu.to_host(v, "f32" if k.startswith("db") else dt) for k, v in out.items()}
+
+    def reference(self):
+        st = _round(self.dtype)
+        v = self.val
+        Z, H, Y = mlp.forward(v["X"], v["W1"], self.b1, v["W2"], self.b2, self.kind, store_z=st, store_h=st, store_y=st)
+        g = mlp.backward(v["dY"], v["X"], v["W1"], Z, H, v["W2"], self.kind, store_g=st, store_dz=st)
+        g.update(Z=Z, H=H, Y=Y)
+        return g
+
+
+CASES = [
+    # q, M, K, N1, N2, dtype, dist, kind
+    (2, 256, 128, 512, 128, "f32", "int", "relu"),          # exact end to end
+    (2, 256, 128, 512, 128, "f32", "uniform", "gelu"),
+    (3, 180, 63, 117, 45, "bf16", "normal", "gelu"),        # ragged: bounds-checked kernels
+    (2, 512, 256, 1024, 256, "bf16", "int", "relu"),        # tuned kernels (small tiles)
+    (2, 1024, 512, 2048, 512, "bf16", "normal", "gelu"),    # tuned kernels, hidden -> 4 x hidden -> hidden
+]
+
+
+@pytest.mark.parametrize("q,M,K,N1,N2,dtype,dist,kind", CASES)
+def test_mlp_block(q, M, K, N1, N2, dtype, dist, kind):
+    blk = Block(q, M, K, N1, N2, dtype, dist, 91, kind)
+    print("mlp block q=%d M=%d K=%d N1=%d N2=%d %s %s %s" % (q, M, K, N1, N2, dtype, dist, kind), flush=True)
+    blk.step()
+    got, ref = blk.results(), blk.reference()
+    for name in ("Z", "H", "Y", "dH", "dZ", "dX", "dW1", "dW2", "db1", "db2"):
+        r = ref[name]
+        if dist == "int" and dtype == "f32":
+            np.testing.assert_array_equal(got[name], r, err_msg=name)
+        else:
+            tol = 1e-5 if dtype == "f32" else 2e-2
+            assert gu.scaled_max_err(got[name], r) <= tol, (name, gu.scaled_max_err(got[name], r))
+
+
+def test_mlp_block_in_a_graph_replays_bit_for_bit():
+    blk = Block(2, 512, 256, 1024, 256, "bf16", "normal", 92, "gelu")
+    blk.step()                         # also the first-call set-up of every kernel, outside the capture
+    eager = {k: v.copy() for k, v in blk.results().items()}
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        blk.step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            blk.step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (blk.z, blk.h, blk.y, blk.dh, blk.dz, blk.dx, blk.dw1, blk.dw2, blk.db1, blk.db2):
+            t.view(torch.uint8).fill_(0xFF)        # eager work between the replays: poison every output
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = blk.results()
+        for k, v in eager.items():
+            np.testing.assert_array_equal(got[k], v, err_msg="replay %d: %s" % (rep, k))
