@@ -607,13 +607,17 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         }
     };
     // The accumulators are not cleared: the first k-step of an item's first K-tile starts the sums from
-    // a zero operand.  That tile body exists in two copies (more K-tiles than one pass or not).
-    auto k_loop = [&]() {
+    // a zero operand.  That tile body exists in several copies (more K-tiles than one pass or not; first
+    // item of the workgroup or not).  `after_stores`: the epilogue of the previous item has issued `stores`
+    // global stores behind this item's first loads; they may stay in flight across the first two tile
+    // barriers (four stages), so the K loop does not wait for the previous item's output to reach memory.
+    auto k_loop = [&](bool after_stores, auto stores_c) {
         using T = std::true_type;
         using F = std::false_type;
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, 1>;
         using Z = std::integral_constant<int, 0>;
+        constexpr int stores = decltype(stores_c)::value;
         const int passes = p.nk / NSTAGE;
         if constexpr (NSTAGE == 2) {
             // nothing is issued between the last load of tile kt+1 and the barrier that waits for it
@@ -633,10 +637,18 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             using S2 = std::integral_constant<int, 2>;
             using S3 = std::integral_constant<int, 3>;
             // in flight across the barrier: tile kt+2, and what this tile body has issued of tile kt+3
-            using STEADY = std::integral_constant<int, LPT + (KS - 1) * LPK>;
+            constexpr int steady = LPT + (KS - 1) * LPK;
+            using STEADY = std::integral_constant<int, steady>;
+            using STEADY_ST = std::integral_constant<int, (steady + stores <= 63 ? steady + stores : 63)>;
+            using DRAIN_ST = std::integral_constant<int, (LPT + stores <= 63 ? LPT + stores : 63)>;
             if (passes > 1) {
-                k_tile(S0{}, T{}, T{}, STEADY{}, T{});
-                k_tile(S1{}, T{}, T{}, STEADY{}, F{});
+                if (after_stores) {
+                    k_tile(S0{}, T{}, T{}, STEADY_ST{}, T{});
+                    k_tile(S1{}, T{}, T{}, STEADY_ST{}, F{});
+                } else {
+                    k_tile(S0{}, T{}, T{}, STEADY{}, T{});
+                    k_tile(S1{}, T{}, T{}, STEADY{}, F{});
+                }
                 k_tile(S2{}, T{}, T{}, STEADY{}, F{});
                 k_tile(S3{}, T{}, T{}, STEADY{}, F{});
                 for (int ps = 2; ps < passes; ++ps) {
@@ -646,11 +658,15 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     k_tile(S3{}, T{}, T{}, STEADY{}, F{});
                 }
                 k_tile(S0{}, T{}, T{}, STEADY{}, F{});
+                k_tile(S1{}, F{}, T{}, std::integral_constant<int, LPT>{}, F{});
+            } else if (after_stores) {
+                k_tile(S0{}, T{}, T{}, STEADY_ST{}, T{});
+                k_tile(S1{}, F{}, T{}, DRAIN_ST{}, F{});
             } else {
                 k_tile(S0{}, T{}, T{}, STEADY{}, T{});
+                k_tile(S1{}, F{}, T{}, std::integral_constant<int, LPT>{}, F{});
             }
-            // rest of the last pass: the pipeline drains
-            k_tile(S1{}, F{}, T{}, std::integral_constant<int, LPT>{}, F{});
+            // rest of the last pass: the pipeline drains (and so have the stores, issued before these loads)
             k_tile(S2{}, F{}, T{}, Z{}, F{});
             k_tile(S3{}, F{}, F{}, Z{}, F{});
         }
@@ -745,8 +761,10 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     setup_sources();
     early_loads();
     finish_prologue(std::integral_constant<int, 0>{});
+    bool after_stores = false;
     while (true) {
-        k_loop();
+        k_loop(after_stores, std::integral_constant<int, STORES>{});
+        after_stores = EPI_SEPARATE;   // only there are the stores younger than the next item's first loads
         const int64_t em0 = m0, en0 = n0;
         const int ebatch = batch, esplit = split;
         item += gridDim.x;
@@ -769,7 +787,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             decode_item(item);
             setup_sources();
             early_loads();
-            finish_prologue(std::integral_constant<int, STORES>{});
+            finish_prologue(std::integral_constant<int, 0>{});   // the stores are older than these loads
         }
     }
 }

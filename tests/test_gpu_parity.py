@@ -226,6 +226,19 @@ def test_rank_share_small_tiles_and_split_k(M, K, N, dist, seed, dtype, out_dtyp
     run_rank_share(1, M, K, N, dtype, dist, seed, (0, 0, 0), out_dtype=out_dtype, twice=True)
 
 
+# ---- more output tiles than the chip holds workgroups: every persistent workgroup takes several items ----
+@pytest.mark.parametrize("M,K,N,dtype,out_dtype", [
+    (3200, 256, 3200, "bf16", "bf16"),      # 625 tiles of 128 x 128 (3200 is no multiple of 256): small-tile path
+    (3200, 256, 3200, "bf16", "f32"),
+    (5120, 256, 5120, "bf16", "bf16"),      # 400 tiles of 256 x 256, one pass over the stages per item
+    (5120, 512, 5120, "fp8_e4m3", "f32"),   # ... fp8, fp32 output (64 stores per wavefront in flight)
+    (4864, 1024, 4608, "bf16", "f32"),      # 342 tiles: workgroups with one and with two items
+])
+@pytest.mark.parametrize("dist,seed", [("normal", 43), ("int", 143)])
+def test_rank_share_many_items_per_workgroup(M, K, N, dtype, out_dtype, dist, seed):
+    run_rank_share(1, M, K, N, dtype, dist, seed, (0, 0, 0), out_dtype=out_dtype, samples=4096, twice=True)
+
+
 # ---- config 2: q=4, h=2048 MLP up-projection, one processor, bf16 ------------------------------
 @pytest.mark.parametrize("dist,seed", [("normal", 2), ("int", 102)])
 @pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
