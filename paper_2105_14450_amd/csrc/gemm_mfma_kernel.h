@@ -287,15 +287,24 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // output tile of one (batch, split).  Consecutive workgroup ids go to different XCDs (id mod 8), and
     // gridDim.x is a multiple of 8 whenever a workgroup gets more than one item, so an item's number mod 8
     // names its XCD too: the numbers are regrouped so that the tiles one XCD runs together form a compact
-    // patch of the tile grid (shared L2).
+    // patch of the tile grid, or belong to the same problem of a batch (shared L2).
     const int tiles_total = p.tiles_m * p.tiles_n;
     const int items = tiles_total * p.y_items;
     int64_t m0, n0;            // origin of the item whose operands are being loaded
     int batch, split;
     auto decode_item = [&](int item) {
-        const int y = item / tiles_total;
-        int tile = item - y * tiles_total;
-        if (tiles_total % 8 == 0) tile = (tile % 8) * (tiles_total / 8) + tile / 8;
+        int y, tile;
+        if (p.y_items % 8 == 0) {
+            // batched launch: every XCD takes whole (batch, split) problems, its CUs the tiles of one
+            // problem after the other, so that a problem's operand panels are fetched into one L2 only
+            const int v = item / 8;
+            y = (v / tiles_total) * 8 + item % 8;
+            tile = v - (v / tiles_total) * tiles_total;
+        } else {
+            y = item / tiles_total;
+            tile = item - y * tiles_total;
+            if (tiles_total % 8 == 0) tile = (tile % 8) * (tiles_total / 8) + tile / 8;
+        }
         const int per_group = p.group_m * p.tiles_n;
         const int gid = tile / per_group;
         const int first_m = gid * p.group_m;
