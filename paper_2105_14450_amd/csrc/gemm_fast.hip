@@ -70,13 +70,26 @@ Plan make_plan(const GemmArgs &g)
     const int64_t tiles256 = fits256 ? (g.Mo / 256) * (g.No / 256) * g.batch : 0;
     if (fits256 && (tiles256 >= (3 * NUM_CU) / 4 || !fits128)) p.tile = 256;
     else p.tile = 128;
-    // Split-K only when the output tiles would leave most CUs idle; the partials cost
-    // splits * Mo * No * 4 bytes of HBM traffic each way, so keep them few and small.
+    // Split-K when it shortens the launch: a split WG walks nk / splits K-tiles, but the fp32 partials
+    // cost splits * Mo * No * 4 bytes each way and a second (reduction) launch.  Estimated per split
+    // count from measured figures (microseconds: K-tile time per workgroup, fixed cost of a workgroup,
+    // fixed cost and bandwidth of the reduction), smallest estimate wins.
     const int64_t tiles = (g.Mo / p.tile) * (g.No / p.tile) * g.batch;
+    const double t_ktile = p.tile == 128 ? 0.14 : 0.44, t_wg = 4.0, t_reduce = 3.0, bytes_per_us = 2.5e6;
+    const double out_bytes = (double)g.Mo * g.No * g.batch;
     int splits = 1;
-    while (tiles * splits * 2 <= NUM_CU / 2 && splits < 16 && nk % (splits * 8) == 0 && nk / (splits * 2) >= 16 &&
-           (int64_t)splits * 2 * g.Mo * g.No * g.batch * 4 <= (32ll << 20))
-        splits *= 2;
+    double best = 0;
+    for (int s = 1; s <= 16; s *= 2) {
+        if (nk % (s * 8) != 0 && s > 1) break;            // every split takes whole passes over the LDS stages
+        if (s > 1 && (double)s * out_bytes * 4 > (double)(64ll << 20)) break;
+        const double rounds = (double)((tiles * s + NUM_CU - 1) / NUM_CU);
+        double t = rounds * ((double)nk / s * t_ktile + t_wg);
+        if (s > 1) t += t_reduce + ((double)s * 4 + 2) * out_bytes / bytes_per_us;
+        if (s == 1 || t < best) {
+            best = t;
+            splits = s;
+        }
+    }
     if ((int64_t)g.batch * splits > 65535) splits = 1;
     p.splits = splits;
     return p;
@@ -119,6 +132,13 @@ int launch_for_layout(const GemmArgs &g, int splits, void *out, int64_t ld, int6
 {
     if (g.a_kmajor && g.b_kmajor && T == 256 && (g.Kc * E::ELT / splits) % 256 == 0)
         return launch_cfg<E, T, T, 128, 2, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
+    if constexpr (std::is_same<E, Bf16>::value && T == 128) {
+        // few small tiles (at most one workgroup per CU): 128-byte K-tiles four stages deep, the whole
+        // LDS for one workgroup: whole cache lines per row and twice the time for a load to arrive
+        if (g.a_kmajor && g.b_kmajor && (g.Mo / T) * (g.No / T) * g.batch * splits <= NUM_CU &&
+            (g.Kc * E::ELT / splits) % 512 == 0)
+            return launch_cfg<E, T, T, 128, 4, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
+    }
     if constexpr (std::is_same<E, Fp8>::value && T == 128) {
         // rows of 128 bytes are too short for the swizzle of an MN-major fp8 tile
         if (!(g.a_kmajor && g.b_kmajor)) return CUBE3D_ENOTIMPL;
