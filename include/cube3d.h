@@ -252,8 +252,9 @@ int virtual_cube_bias_bwd(const cube3d_desc *desc, const void *dY_shards, void *
  *   bwd_dx:  dY_shards [Ms, Nb], W_shards [Kb, Ns] -> dX_shards [Ms, Kb]   (Algorithm 2 line 1)
  *   bwd_dw:  X_shards [Ms, Kb], dY_shards [Ms, Nb] -> dW_shards [Kb, Ns]   (Algorithm 2 line 2)
  * fp8 inputs are scaled by the product of the two operand scales.  Needs no workspace.
- * Any valid descriptor is accepted; shapes that fit the tuned kernel's tiles (all of M, K, N
- * multiples of 128, shard sizes multiples of 32, bf16 or fp8 inputs) run on it, the rest on the
+ * Any valid descriptor is accepted; shapes that fit the tuned kernel's tiles (bf16 or fp8 inputs,
+ * M, K, N multiples of 128, the contraction length a multiple of four 64-byte K-tiles, shard
+ * sizes multiples of 32, cube buffers shorter than 4 GB) run on it, the rest on the
  * bounds-checked kernel.
  */
 int virtual_cube_linear_fwd(const cube3d_desc *desc, const void *X_shards, const void *W_shards, const void *bias_diag,
