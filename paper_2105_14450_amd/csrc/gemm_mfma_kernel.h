@@ -323,7 +323,13 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     const char *a_base, *b_base;
     unsigned a_voff[ATile::CPW], b_voff[BTile::CPW];
     int64_t a_step = 0, b_step = 0;              // bytes from one K-tile to the next (plain operands)
-    int a_c1 = 0, a_c2 = 0, b_c1 = 0, b_c2 = 0;  // MAPPED: position of the K walk inside the current block / shard
+    // MAPPED: state of an operand's walk along the contraction index
+    struct Walk {
+        int c1, c2;            // position inside the current block / shard
+        int m1, m2;            // masks of the pending step: walked off a block / off a shard
+        int64_t delta;         // bytes to add
+    };
+    Walk wa{0, 0, 0, 0, 0}, wb{0, 0, 0, 0, 0};
     auto setup_sources = [&]() {
     if constexpr (!MAPPED) {
         const int64_t kt0 = (int64_t)split * p.nk;   // first K-tile of this split
@@ -343,7 +349,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         constexpr int EPS = 16 / E::ELT;   // elements per 16-byte slot
         a_base = static_cast<const char *>(p.A);
         b_base = static_cast<const char *>(p.B);
-        a_c1 = a_c2 = b_c1 = b_c2 = 0;
+        wa.c1 = wa.c2 = wb.c1 = wb.c2 = 0;
         {
             const int first = wave * ATile::RPC + lane / ATile::SPR;   // tile row (K-major) or k-row (MN-major)
 #pragma unroll
@@ -388,22 +394,38 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // Move an operand's scalar pointer to the next K-tile.  MAPPED: the walk along the contraction
     // index steps through shards and blocks; the corrections are selected with masks, because a
     // branch in the K loop holds up the MFMA stream far longer than a dozen scalar instructions.
-    auto advance = [&](const char *&base, int64_t plain_step, const KWalk &w, int &c1, int &c2) {
-        if constexpr (!MAPPED) {
-            base += plain_step;
-        } else {
+    // Even so the scalar work of one step is more than fits behind one MFMA, so inside the K loop it
+    // is dealt out in three parts over three gaps (walk_part), and only the final add sits behind
+    // the operand's last load (walk_apply).
+    auto walk_part = [&](Walk &w, const KWalk &k, int part) {
+        if constexpr (MAPPED) {
             constexpr int KPT = BKB / E::ELT;   // contraction indices per K-tile
-            c1 += KPT;
-            c2 += KPT;
-            const int64_t off_block = eq_mask(c1, w.P1);                 // all ones: the tile walked off a block
-            const int64_t off_shard = eq_mask(c2, w.P2) & ~off_block;    // ... off a shard inside the block
-            base += (w.step + (w.jump1 & off_block) + (w.jump2 & off_shard)) * E::ELT;
-            c1 &= (int)~off_block;
-            c2 &= (int)~(off_block | off_shard);
+            if (part == 0) {
+                w.c1 += KPT;
+                w.c2 += KPT;
+                w.m1 = eq_mask(w.c1, k.P1);
+                w.m2 = eq_mask(w.c2, k.P2) & ~w.m1;
+            } else if (part == 1) {
+                w.delta = (k.step + (k.jump1 & (int64_t)w.m1) + (k.jump2 & (int64_t)w.m2)) * E::ELT;
+            } else {
+                w.c1 &= ~w.m1;
+                w.c2 &= ~(w.m1 | w.m2);
+            }
         }
     };
-    auto advance_a = [&]() { advance(a_base, a_step, p.ka, a_c1, a_c2); };
-    auto advance_b = [&]() { advance(b_base, b_step, p.kb, b_c1, b_c2); };
+    auto walk_apply = [&](const char *&base, int64_t plain_step, const Walk &w) {
+        if constexpr (!MAPPED) base += plain_step;
+        else base += w.delta;
+    };
+    // the whole step at once (prologue)
+    auto advance_a = [&]() {
+        walk_part(wa, p.ka, 0); walk_part(wa, p.ka, 1); walk_part(wa, p.ka, 2);
+        walk_apply(a_base, a_step, wa);
+    };
+    auto advance_b = [&]() {
+        walk_part(wb, p.kb, 0); walk_part(wb, p.kb, 1); walk_part(wb, p.kb, 2);
+        walk_apply(b_base, b_step, wb);
+    };
 
     // ---- lane-constant LDS addresses of the fragment reads; every read adds an immediate -------------
     // K-major operand: one register per 16-byte piece of a k-step; MN-major operand: one per 32-wide
@@ -575,6 +597,26 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     acc[i][j] = E::mfma(frag_b(cur, j), frag_a(cur, i), acc[i][j]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                if (MAPPED) {
+                    // scalar work of the K walk: the operand whose pointer moves first in this tile body
+                    // (A with four stages, B with two) in the first twelfth-steps, the other from the middle
+                    const int f = ks * NM + g;
+                    constexpr int TOTG = KS * NM;
+#pragma unroll
+                    for (int part = 0; part < 3; ++part) {
+                        const bool first_moves = NSTAGE == 2 ? has_next : more;    // its loads are issued at all
+                        const bool second_moves = more;
+                        if (f == (part * TOTG) / 12 && first_moves) {
+                            if (NSTAGE == 2) walk_part(wb, p.kb, part);
+                            else walk_part(wa, p.ka, part);
+                        }
+                        if (f == TOTG / 2 + (part * TOTG) / 12 && second_moves) {
+                            if (NSTAGE == 2) walk_part(wa, p.ka, part);
+                            else walk_part(wb, p.kb, part);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 if (do_read) {
 #pragma unroll
                     for (int r = 0; r < NRD; ++r) {
@@ -589,8 +631,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                         if (((2 * l + 1) * NM) / (2 * LPK) != g) continue;
                         issue_load(ks * LPK + l, pre);
                         // behind an operand's last load of the tile: its pointer moves on
-                        if (ks * LPK + l == ATile::CPW - 1) advance_a();
-                        if (ks * LPK + l == LPT - 1) advance_b();
+                        if (ks * LPK + l == ATile::CPW - 1) walk_apply(a_base, a_step, wa);
+                        if (ks * LPK + l == LPT - 1) walk_apply(b_base, b_step, wb);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -599,7 +641,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     for (int l = 0; l < BTile::CPW; ++l) {
                         if (((2 * l + 1) * NM) / (2 * BTile::CPW) != g) continue;
                         issue_load(ATile::CPW + l, next);
-                        if (l == BTile::CPW - 1) advance_b();
+                        if (l == BTile::CPW - 1) walk_apply(b_base, b_step, wb);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -608,7 +650,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     for (int l = 0; l < ATile::CPW; ++l) {
                         if (((2 * l + 1) * NM) / (2 * ATile::CPW) != g) continue;
                         issue_load(l, stage);
-                        if (l == ATile::CPW - 1) advance_a();
+                        if (l == ATile::CPW - 1) walk_apply(a_base, a_step, wa);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
