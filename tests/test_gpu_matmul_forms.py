@@ -172,3 +172,44 @@ def test_every_placement_moves_bits_like_the_oracle(q, dtype):
                 c3.virtual_cube_matrix_reduce_scatter(mo, gu.CODE[dtype], gu.to_device(part_raw), out)
                 ref = d3.reduce_scatter(vals.astype(np.float64), q, pl)
                 np.testing.assert_array_equal(gu.to_host(out, "f32"), ref.reshape(gu.to_host(out, "f32").shape))
+
+
+def test_shape_sweep_of_the_batched_product():
+    """Many tile-aligned and ragged block shapes through cube3d_matmul_blocks (q = 1: one problem,
+    q = 2: eight problems per launch), all three forms, bf16 and fp8, fp32 and bf16 results: every
+    tile size, K-tile depth, split and work-item count the plan can choose.  Integer data: the
+    sampled entries must equal the oracle's exact sums (rounded once when the result is bf16)."""
+    from oracle import matmul as om
+    rng = np.random.default_rng(2024)
+    sizes = [128, 256, 384, 512, 640, 768, 1024, 1280, 1536, 200, 72]
+    ks = [128, 256, 384, 512, 1024, 2048, 4096, 96]
+    done = 0
+    for trial in range(60):
+        q = int(rng.choice([1, 1, 2]))
+        m, n, k = int(rng.choice(sizes)), int(rng.choice(sizes)), int(rng.choice(ks))
+        form = str(rng.choice(["AB", "ABT", "ATB"]))
+        dtype = str(rng.choice(["bf16", "bf16", "fp8_e4m3"]))
+        out_dtype = str(rng.choice(["f32", "bf16"]))
+        nb = q ** 3
+        sa, sb, _ = _shapes(form, m, n, k)
+        a_raw, _ = synth.store(synth.draw((nb,) + sa, "int", 300 + trial, synth.TID_X), dtype, True)
+        b_raw, _ = synth.store(synth.draw((nb,) + sb, "int", 300 + trial, synth.TID_W), dtype, True)
+        mm = c3.make_matmul(q, FORM[form], m, n, k, gu.CODE[dtype], gu.CODE[out_dtype])
+        out = gu.empty((nb, m, n), out_dtype)
+        nws = c3.cube3d_matmul_workspace_bytes(mm)
+        ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda") if nws else None
+        print("sweep %d: q=%d %s m=%d n=%d k=%d %s -> %s ws=%d" % (trial, q, form, m, n, k, dtype, out_dtype, nws), flush=True)
+        c3.cube3d_matmul_blocks(mm, gu.to_device(a_raw), gu.to_device(b_raw), out, ws)
+        torch.cuda.synchronize()
+        got = gu.to_host(out, out_dtype)
+        for r in (0, nb - 1):
+            A, B = numfmt.decode(a_raw[r], dtype), numfmt.decode(b_raw[r], dtype)
+            rows, cols = rng.integers(0, m, 512), rng.integers(0, n, 512)
+            rows[:4], cols[:4] = [0, 0, m - 1, m - 1], [0, n - 1, 0, n - 1]
+            fn = {"AB": om.forward_at, "ABT": om.backward_dx_at, "ATB": om.backward_dw_at}[form]
+            ref = fn(A, B, rows, cols)
+            want = numfmt.round_to_bf16(ref) if out_dtype == "bf16" else ref
+            np.testing.assert_array_equal(got[r][rows, cols], want, err_msg="trial %d block %d" % (trial, r))
+        assert np.all(np.isfinite(got))
+        done += 1
+    assert done == 60
