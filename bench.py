@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time aimed at by the cpu_baseline sample")
+    ap.add_argument("--config3-linear", default=None, choices=[c[0] for c in CONFIG3],
+                    help="restrict the config-3 virtual cube to one linear (clean per-kernel profiler counters)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for scaling profiler byte counters)")
     return ap.parse_args()
@@ -219,13 +221,14 @@ def main():
             except Exception as exc:   # a failed side run must not lose the headline line
                 extra[name] = {"error": repr(exc)}
         try:
-            extra["config3"] = bench_virtual_cube(c3, synth, torch, np, timed)
+            extra["config3"] = bench_virtual_cube(c3, synth, torch, np, timed, args.config3_linear)
         except Exception as exc:
             extra["config3"] = {"error": repr(exc)}
-        try:
-            extra["config3"]["layer_chain"] = bench_layer_chain(c3, torch, stream)
-        except Exception as exc:
-            extra["config3"]["layer_chain"] = {"error": repr(exc)}
+        if args.config3_linear is None:
+            try:
+                extra["config3"]["layer_chain"] = bench_layer_chain(c3, torch, stream)
+            except Exception as exc:
+                extra["config3"]["layer_chain"] = {"error": repr(exc)}
         out["per_config"] = extra
 
     # ---- the oracle on the host cores, bounded sample -------------------------------------------------
@@ -236,7 +239,7 @@ def main():
     return 0
 
 
-def bench_virtual_cube(c3, synth, torch, np, timed):
+def bench_virtual_cube(c3, synth, torch, np, timed, only=None):
     """Config 3: the four linears of one Transformer layer on the 64-processor virtual cube (q = 4,
     8192 tokens, bf16): batched products over all ranks plus the on-HBM gathers and reduce-scatters."""
     q, M = 4, 8192
@@ -245,6 +248,8 @@ def bench_virtual_cube(c3, synth, torch, np, timed):
     tot_flop, tot_ms = 0.0, 0.0
     cube_flop, cube_ms = 0.0, 0.0
     for name, K, N, ax in CONFIG3:
+        if only is not None and name != only:
+            continue
         in_axis = c3.AXIS_Y if ax == "y" else c3.AXIS_Z
         out_axis = c3.AXIS_Z if ax == "y" else c3.AXIS_Y
         d = c3.make_desc(q, M, K, N, in_dtype=c3.BF16, out_dtype=c3.F32, shard_dtype=c3.BF16, in_axis=in_axis)
