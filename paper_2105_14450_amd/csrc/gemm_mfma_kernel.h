@@ -884,7 +884,7 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
     p.y_items = g.batch * splits;
     // persistent workgroups: as many as the chip holds at once (a multiple of 8), or one per item
     const int64_t items = (int64_t)p.tiles_m * p.tiles_n * p.y_items;
-    const int64_t resident = 256 * (BIG ? 1 : 2);
+    const int64_t resident = 256 * (LDS > 80 * 1024 ? 1 : 2);   // workgroups the 160 KB of a CU's LDS hold
     if (items >= (1ll << 31)) return CUBE3D_ENOTIMPL;
     dim3 grid((unsigned)(items < resident ? items : resident), 1, 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), LDS, g.stream, p);
