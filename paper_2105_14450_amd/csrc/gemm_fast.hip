@@ -132,7 +132,7 @@ int launch_for_layout(const GemmArgs &g, int splits, void *out, int64_t ld, int6
 {
     if (g.a_kmajor && g.b_kmajor && T == 256 && (g.Kc * E::ELT / splits) % 256 == 0)
         return launch_cfg<E, T, T, 128, 2, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
-    if constexpr (std::is_same<E, Bf16>::value && T == 128) {
+    if constexpr (T == 128) {
         // small tiles of the dX layout: 128-byte K-tiles four stages deep, the whole LDS for one workgroup
         // per CU: whole cache lines per row, half as many barriers and twice the time for a load to
         // arrive (337 against 522 cycles per 64 bytes of K, also where two shallower workgroups would fit)
