@@ -174,26 +174,36 @@ def test_every_placement_moves_bits_like_the_oracle(q, dtype):
                 np.testing.assert_array_equal(gu.to_host(out, "f32"), ref.reshape(gu.to_host(out, "f32").shape))
 
 
+def test_shape_sweep_many_items_per_workgroup():
+    """Larger single problems whose tile counts exceed the chip's resident workgroups by odd factors
+    (persistent workgroups with unequal item counts, tile grids that are no multiple of 8), sampled
+    against the oracle's exact sums on integer data."""
+    _sweep(12, [2304, 2560, 2816, 3072, 3328, 4352], [256, 512, 1024], [1], 500, seed=77)
+
+
 def test_shape_sweep_of_the_batched_product():
     """Many tile-aligned and ragged block shapes through cube3d_matmul_blocks (q = 1: one problem,
     q = 2: eight problems per launch), all three forms, bf16 and fp8, fp32 and bf16 results: every
     tile size, K-tile depth, split and work-item count the plan can choose.  Integer data: the
     sampled entries must equal the oracle's exact sums (rounded once when the result is bf16)."""
+    _sweep(60, [128, 256, 384, 512, 640, 768, 1024, 1280, 1536, 200, 72], [128, 256, 384, 512, 1024, 2048, 4096, 96],
+           [1, 1, 2], 300, seed=2024)
+
+
+def _sweep(trials, sizes, ks, qs, seed0, seed):
     from oracle import matmul as om
-    rng = np.random.default_rng(2024)
-    sizes = [128, 256, 384, 512, 640, 768, 1024, 1280, 1536, 200, 72]
-    ks = [128, 256, 384, 512, 1024, 2048, 4096, 96]
+    rng = np.random.default_rng(seed)
     done = 0
-    for trial in range(60):
-        q = int(rng.choice([1, 1, 2]))
+    for trial in range(trials):
+        q = int(rng.choice(qs))
         m, n, k = int(rng.choice(sizes)), int(rng.choice(sizes)), int(rng.choice(ks))
         form = str(rng.choice(["AB", "ABT", "ATB"]))
         dtype = str(rng.choice(["bf16", "bf16", "fp8_e4m3"]))
         out_dtype = str(rng.choice(["f32", "bf16"]))
         nb = q ** 3
         sa, sb, _ = _shapes(form, m, n, k)
-        a_raw, _ = synth.store(synth.draw((nb,) + sa, "int", 300 + trial, synth.TID_X), dtype, True)
-        b_raw, _ = synth.store(synth.draw((nb,) + sb, "int", 300 + trial, synth.TID_W), dtype, True)
+        a_raw, _ = synth.store(synth.draw((nb,) + sa, "int", seed0 + trial, synth.TID_X), dtype, True)
+        b_raw, _ = synth.store(synth.draw((nb,) + sb, "int", seed0 + trial, synth.TID_W), dtype, True)
         mm = c3.make_matmul(q, FORM[form], m, n, k, gu.CODE[dtype], gu.CODE[out_dtype])
         out = gu.empty((nb, m, n), out_dtype)
         nws = c3.cube3d_matmul_workspace_bytes(mm)
@@ -212,4 +222,4 @@ def test_shape_sweep_of_the_batched_product():
             np.testing.assert_array_equal(got[r][rows, cols], want, err_msg="trial %d block %d" % (trial, r))
         assert np.all(np.isfinite(got))
         done += 1
-    assert done == 60
+    assert done == trials
