@@ -587,7 +587,9 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             const bool do_read = !last || has_next;
 #pragma unroll
             for (int g = 0; g < NM; ++g) {
-                const int i = g / TN, j = g % TN;
+                // serpentine over the sub-tile's blocks: from one MFMA to the next only one operand changes,
+                // also at the end of a block row (fewer operand-bus toggles: the chip is power-limited)
+                const int i = g / TN, j = (i & 1) ? TN - 1 - g % TN : g % TN;
                 if (first && ks == 0) {
                     f32x16 zero;
 #pragma unroll
