@@ -338,6 +338,27 @@ typedef struct cube3d_matmul {
 } cube3d_matmul;
 
 size_t cube3d_matmul_workspace_bytes(const cube3d_matmul *mm);
+
+/*
+ * One of the three products over the whole virtual cube with the pieces read and written in
+ * place: what all-gather, all-gather, cube3d_matmul_blocks and reduce-scatter compute together
+ * (Algorithms 1, 3, 5, and each line of Algorithms 2, 4, 6), without gathered copies and without
+ * partial products.  Every index of the full matrices has one fixed place in the cube buffers
+ * (Section 3.1.1), so the gathers are address arithmetic and the reduce-scatter's sum is the
+ * contraction loop running on across the pieces: each result element is accumulated in fp32 over
+ * the whole contraction and rounded once to C->dtype.
+ *   form = AB  : A [m, k], B [k, n];  ABT : A [m, k], B [n, k];  ATB : A [k, m], B [k, n]
+ *   -> C [m, n]  (global sizes, taken from the three descriptors, which must agree)
+ * A and B have the same dtype (F32, BF16 or FP8_E4M3; fp8 results are multiplied by
+ * scale_a * scale_b, scales ignored otherwise); C->dtype is F32 or BF16; all three the same q.
+ * Any placements are accepted (the result is the plain product of the full matrices wherever the
+ * pieces live); with the directions of the paper's algorithms this is their result.  Needs no
+ * workspace.  Results equal those of the four-step path up to fp32 summation order (bit for bit on
+ * small-integer data).
+ */
+int virtual_cube_matmul(int form, const cube3d_matrix *A, const cube3d_matrix *B, const cube3d_matrix *C,
+                        float scale_a, float scale_b, const void *A_pieces, const void *B_pieces, void *C_pieces,
+                        void *stream);
 int cube3d_matmul_blocks(const cube3d_matmul *mm, const void *A_blocks, const void *B_blocks, void *C_blocks,
                          void *workspace, size_t workspace_bytes, void *stream);
 

@@ -125,6 +125,8 @@ def load():
     lib.cube3d_matmul_workspace_bytes.restype = sz
     lib.cube3d_matmul_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.cube3d_matmul_blocks.restype = ci
+    lib.virtual_cube_matmul.argtypes = [ci, mp, mp, mp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
+    lib.virtual_cube_matmul.restype = ci
     lib.cube3d_activation_fwd.argtypes = [ci, ci, ci, ctypes.c_int64, vp, vp, vp]
     lib.cube3d_activation_fwd.restype = ci
     lib.cube3d_activation_bwd.argtypes = [ci, ci, ci, ci, ctypes.c_int64, vp, vp, vp, vp]
@@ -142,7 +144,7 @@ EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", 
            "virtual_cube_bias_bwd", "virtual_cube_linear_fwd", "virtual_cube_linear_bwd_dx",
            "virtual_cube_linear_bwd_dw", "virtual_cube_matrix_scatter", "virtual_cube_matrix_assemble",
            "virtual_cube_matrix_gather", "virtual_cube_matrix_reduce_scatter", "cube3d_matmul_workspace_bytes",
-           "cube3d_matmul_blocks", "cube3d_activation_fwd", "cube3d_activation_bwd", "cube3d_status_string",
+           "cube3d_matmul_blocks", "virtual_cube_matmul", "cube3d_activation_fwd", "cube3d_activation_bwd", "cube3d_status_string",
            "cube3d_version")
 
 
@@ -306,3 +308,10 @@ def cube3d_activation_bwd(kind, z_dtype, dh_dtype, dz_dtype, z, dh, dz, stream=N
     _check(load().cube3d_activation_bwd(kind, z_dtype, dh_dtype, dz_dtype, z.numel(), _ptr(z), _ptr(dh), _ptr(dz),
                                         _stream(stream)), "cube3d_activation_bwd")
     return dz
+
+
+def virtual_cube_matmul(form, A, B, C, A_pieces, B_pieces, C_pieces, scale_a=1.0, scale_b=1.0, stream=None):
+    _check(load().virtual_cube_matmul(form, ctypes.byref(A), ctypes.byref(B), ctypes.byref(C), scale_a, scale_b,
+                                      _ptr(A_pieces), _ptr(B_pieces), _ptr(C_pieces), _stream(stream)),
+           "virtual_cube_matmul")
+    return C_pieces

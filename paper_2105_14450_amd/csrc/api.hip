@@ -380,6 +380,28 @@ int check_matrix(const cube3d_matrix *m, CubeGeom *g)
     return CUBE3D_OK;
 }
 
+// Where a row / column index of the full matrix lands in the cube buffer of pieces (processor
+// number r = (i*q + j)*q + l, pieces [pRs, pCs] packed back to back): block index along the row /
+// column direction, piece index along the remaining direction when that direction cuts this index.
+int64_t axis_rank_stride(const CubeGeom &g, int axis) { return axis == 0 ? (int64_t)g.q * g.q : axis == 1 ? g.q : 1; }
+
+AxisMap place_row_map(const CubeGeom &g)
+{
+    const int64_t piece = g.pRs * g.pCs;
+    if (g.p_split_rows)
+        return AxisMap{(int32_t)g.pRb, (int32_t)g.pRs, axis_rank_stride(g, g.p_ra) * piece, axis_rank_stride(g, g.p_sa) * piece,
+                       g.pCs};
+    return AxisMap{(int32_t)g.pRb, (int32_t)g.pRb, axis_rank_stride(g, g.p_ra) * piece, 0, g.pCs};
+}
+
+AxisMap place_col_map(const CubeGeom &g)
+{
+    const int64_t piece = g.pRs * g.pCs;
+    if (!g.p_split_rows)
+        return AxisMap{(int32_t)g.pCb, (int32_t)g.pCs, axis_rank_stride(g, g.p_ca) * piece, axis_rank_stride(g, g.p_sa) * piece, 1};
+    return AxisMap{(int32_t)g.pCb, (int32_t)g.pCb, axis_rank_stride(g, g.p_ca) * piece, 0, 1};
+}
+
 int matrix_move(const cube3d_matrix *m, int mode, const void *src, void *dst, void *stream)
 {
     CubeGeom g;
@@ -450,6 +472,56 @@ int virtual_cube_matrix_reduce_scatter(const cube3d_matrix *m, int partial_dtype
     if (!partials || !pieces || misaligned(partials) || misaligned(pieces)) return CUBE3D_EINVAL;
     return cube_reduce(g, MV_PLACE_REDUCE, partial_dtype, m->dtype, partials, pieces, nullptr,
                        static_cast<hipStream_t>(stream));
+}
+
+int virtual_cube_matmul(int form, const cube3d_matrix *A, const cube3d_matrix *B, const cube3d_matrix *C,
+                        float scale_a, float scale_b, const void *A_pieces, const void *B_pieces, void *C_pieces,
+                        void *stream)
+{
+    if (form != CUBE3D_FORM_AB && form != CUBE3D_FORM_ABT && form != CUBE3D_FORM_ATB) return CUBE3D_EINVAL;
+    CubeGeom ga, gb, gc;
+    int rc = check_matrix(A, &ga);
+    if (rc == CUBE3D_OK) rc = check_matrix(B, &gb);
+    if (rc == CUBE3D_OK) rc = check_matrix(C, &gc);
+    if (rc != CUBE3D_OK) return rc;
+    if (A->q != B->q || A->q != C->q) return CUBE3D_EINVAL;
+    if (A->dtype != B->dtype) return CUBE3D_EDTYPE;
+    if (C->dtype != CUBE3D_F32 && C->dtype != CUBE3D_BF16) return CUBE3D_EDTYPE;
+    const bool fp8 = A->dtype == CUBE3D_FP8_E4M3;
+    if (fp8)
+        for (float v : {scale_a, scale_b})
+            if (!(v > 0.f) || v > 3.0e38f) return CUBE3D_EINVAL;
+    // global sizes: result [m, n], contraction k
+    const int64_t m = form == CUBE3D_FORM_ATB ? A->cols : A->rows, ka = form == CUBE3D_FORM_ATB ? A->rows : A->cols;
+    const int64_t n = form == CUBE3D_FORM_ABT ? B->rows : B->cols, kb = form == CUBE3D_FORM_ABT ? B->cols : B->rows;
+    if (ka != kb || C->rows != m || C->cols != n) return CUBE3D_ESHAPE;
+    if (m >= (1ll << 31) || n >= (1ll << 31) || ka >= (1ll << 31)) return CUBE3D_ESHAPE;
+    if (!A_pieces || !B_pieces || !C_pieces || misaligned(A_pieces) || misaligned(B_pieces) || misaligned(C_pieces))
+        return CUBE3D_EINVAL;
+    GemmMaps mp{};
+    const bool a_t = form == CUBE3D_FORM_ATB, b_t = form == CUBE3D_FORM_ABT;
+    mp.a_mn = a_t ? place_col_map(ga) : place_row_map(ga);
+    mp.a_k = a_t ? place_row_map(ga) : place_col_map(ga);
+    mp.b_mn = b_t ? place_row_map(gb) : place_col_map(gb);
+    mp.b_k = b_t ? place_col_map(gb) : place_row_map(gb);
+    mp.c_m = place_row_map(gc);
+    mp.c_n = place_col_map(gc);
+    mp.bias = nullptr;
+    mp.bias_n = mp.c_n;
+    GemmArgs a{};
+    a.A = A_pieces; a.B = B_pieces; a.C = C_pieces;
+    a.batch = 1;
+    a.Mo = m; a.No = n; a.Kc = ka;
+    a.a_kmajor = !a_t;
+    a.b_kmajor = b_t;
+    a.in_dtype = A->dtype;
+    a.out_dtype = C->dtype;
+    a.alpha = fp8 ? scale_a * scale_b : 1.f;
+    a.stream = static_cast<hipStream_t>(stream);
+    a.maps = &mp;
+    rc = gemm_fast(a);
+    if (rc != CUBE3D_ENOTIMPL) return rc;
+    return gemm_generic(a);
 }
 
 size_t cube3d_matmul_workspace_bytes(const cube3d_matmul *mm)

@@ -184,6 +184,25 @@ def test_matrix_and_matmul_argument_errors(lib):
         a.update(kw)
         return c3.make_matmul(**a)
 
+    vm = lib.virtual_cube_matmul
+    A = mat(rows=16, cols=8)                                                         # [m, k]
+    B = mat(rows=8, cols=16, row_axis=c3.AXIS_Z, col_axis=c3.AXIS_Y, split=c3.SPLIT_COLS)   # [k, n]
+    C = mat(rows=16, cols=16, row_axis=c3.AXIS_X, col_axis=c3.AXIS_Y)                # [m, n]
+    ok = lambda f_, a_, b_, c_, pa=FAKE, pb=FAKE, pc_=FAKE, sa=1.0, sb=1.0: vm(
+        f_, ctypes.byref(a_) if a_ is not None else None, ctypes.byref(b_), ctypes.byref(c_), sa, sb, pa, pb, pc_, None)
+    assert ok(3, A, B, C) == c3.EINVAL
+    assert ok(c3.FORM_AB, None, B, C) == c3.EINVAL
+    assert ok(c3.FORM_AB, A, B, mat(rows=16, cols=32)) == c3.ESHAPE               # result size disagrees
+    assert ok(c3.FORM_ABT, A, B, C) == c3.ESHAPE                                   # contraction lengths disagree
+    assert ok(c3.FORM_AB, A, mat(rows=8, cols=16, q=1), C) == c3.EINVAL           # different cubes
+    assert ok(c3.FORM_AB, A, mat(rows=8, cols=16, dtype=c3.BF16, split=c3.SPLIT_COLS), C) == c3.EDTYPE
+    assert ok(c3.FORM_AB, A, B, mat(rows=16, cols=16, dtype=c3.FP8_E4M3)) == c3.EDTYPE
+    assert ok(c3.FORM_AB, A, B, C, pa=None) == c3.EINVAL
+    assert ok(c3.FORM_AB, A, B, C, pc_=ODD) == c3.EINVAL
+    f8a, f8b = mat(rows=16, cols=8, dtype=c3.FP8_E4M3), mat(rows=8, cols=16, dtype=c3.FP8_E4M3, row_axis=c3.AXIS_Z,
+                                                            col_axis=c3.AXIS_Y, split=c3.SPLIT_COLS)
+    assert ok(c3.FORM_AB, f8a, f8b, C, sa=-1.0) == c3.EINVAL
+
     f = lib.cube3d_matmul_blocks
     assert f(None, FAKE, FAKE, FAKE, None, 0, None) == c3.EINVAL
     assert f(ctypes.byref(mm(form=3)), FAKE, FAKE, FAKE, None, 0, None) == c3.EINVAL

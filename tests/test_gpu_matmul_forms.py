@@ -72,6 +72,14 @@ def _matmul_3d(q, form, a_pieces, ma, pa, sa, b_pieces, mb, pb, sb, pc, sc, dtyp
     return mc, out
 
 
+def _matmul_in_place(q, form, a_pieces, ma, b_pieces, mb, pc, sc, scales, shard_dtype):
+    """The same product as one call over the whole cube, pieces read and written in place."""
+    mc = _matrix(q, sc, pc, shard_dtype)
+    out = gu.empty((q ** 3,) + pc.shard_shape(q, *sc), shard_dtype)
+    c3.virtual_cube_matmul(FORM[form], ma, mb, mc, a_pieces, b_pieces, out, scales[0], scales[1])
+    return mc, out
+
+
 def _assemble(mc, pieces, shape, dtype):
     full = gu.empty(shape, dtype)
     c3.virtual_cube_matrix_assemble(mc, pieces, full)
@@ -127,6 +135,10 @@ def test_forward_and_backward(q, form, u, v, w, dtype, out_dtype, shard_dtype, d
     C = _assemble(mc, c_pieces, sc, shard_dtype)
     ref = d3.unshard(d3.forward(form, A, B, q), q, pc, *sc)
     _compare(C, ref, exact, out_dtype, shard_dtype, tol, "%s forward" % form)
+    mc2, c2 = _matmul_in_place(q, form, a_pieces, ma, b_pieces, mb, pc, sc, (a_scale, b_scale), shard_dtype)
+    _compare(_assemble(mc2, c2, sc, shard_dtype), ref, exact, "f32", shard_dtype, tol, "%s forward, in place" % form)
+    if exact and out_dtype == "f32":   # same exact sums, same single rounding: the two paths agree bit for bit
+        np.testing.assert_array_equal(gu.raw_host(c2), gu.raw_host(c_pieces))
 
     # backward: Algorithm 2 / 4 / 6, each line one more 3-D product with the placements as stored
     da_ref, db_ref = d3.backward(form, G, A, B, q)
@@ -142,6 +154,9 @@ def test_forward_and_backward(q, form, u, v, w, dtype, out_dtype, shard_dtype, d
         got = _assemble(mo, out, so, shard_dtype)
         ref = d3.unshard(ref_sh, q, plo, *so)
         _compare(got, ref, exact, out_dtype, shard_dtype, tol, "%s backward d%s" % (form, name))
+        mo2, out2 = _matmul_in_place(q, f2, p1, m1, p2, m2, plo, so, (sc1, sc2), shard_dtype)
+        _compare(_assemble(mo2, out2, so, shard_dtype), ref, exact, "f32", shard_dtype, tol,
+                 "%s backward d%s, in place" % (form, name))
 
 
 @pytest.mark.parametrize("q", [1, 2, 3])
