@@ -42,11 +42,19 @@
  *
  * Ownership and execution.  Every data pointer is DEVICE memory owned by the
  * caller; `desc` is HOST memory read during the call only.  The library
- * allocates nothing, keeps no state between calls, never synchronises the
- * device and enqueues work only on the caller's stream (`stream` is a
- * hipStream_t passed as void*; NULL = the default stream).  Outputs are fully
- * overwritten.  Inputs and outputs must not overlap.  Data pointers must be
- * 16-byte aligned.
+ * allocates nothing, never synchronises the device and enqueues work only on
+ * the caller's stream (`stream` is a hipStream_t passed as void*; NULL = the
+ * default stream).  Outputs are fully overwritten.  Inputs and outputs must
+ * not overlap.  Data pointers must be 16-byte aligned.
+ *
+ * State.  No result depends on an earlier call.  What the library keeps per
+ * device, guarded by locks (calls may come from several threads): the number
+ * of compute units, read once from the device, and one flag per kernel
+ * variant saying that its one-time set-up (raising the kernel's dynamic LDS
+ * limit with hipFuncSetAttribute) has been done on that device.  A variant is
+ * set up on its first use, or all at once by cube3d_init(); call cube3d_init()
+ * on each device before capturing calls into a HIP graph, so that no set-up
+ * falls into the capture.
  *
  * Errors.  Every call returns a cube3d_status; 0 is success.  All argument
  * checks happen on the host before anything is enqueued, so a failed call has
@@ -384,6 +392,11 @@ typedef enum cube3d_activation {
 int cube3d_activation_fwd(int kind, int z_dtype, int h_dtype, int64_t n, const void *z, void *h, void *stream);
 int cube3d_activation_bwd(int kind, int z_dtype, int dh_dtype, int dz_dtype, int64_t n, const void *z, const void *dh,
                           void *dz, void *stream);
+
+/* One-time set-up of every kernel variant on the calling thread's current device (optional:
+ * a variant is otherwise set up on its first use).  Enqueues nothing.  CUBE3D_ELAUNCH when
+ * there is no device or the runtime refuses. */
+int cube3d_init(void);
 
 const char *cube3d_status_string(int status);
 int cube3d_version(void);

@@ -134,6 +134,8 @@ def load():
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
     lib.cube3d_version.restype = ci
+    lib.cube3d_init.argtypes = []
+    lib.cube3d_init.restype = ci
     _lib = lib
     return lib
 
@@ -145,7 +147,7 @@ EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", 
            "virtual_cube_linear_bwd_dw", "virtual_cube_matrix_scatter", "virtual_cube_matrix_assemble",
            "virtual_cube_matrix_gather", "virtual_cube_matrix_reduce_scatter", "cube3d_matmul_workspace_bytes",
            "cube3d_matmul_blocks", "virtual_cube_matmul", "cube3d_activation_fwd", "cube3d_activation_bwd", "cube3d_status_string",
-           "cube3d_version")
+           "cube3d_version", "cube3d_init")
 
 
 def status_string(status: int) -> str:
@@ -315,3 +317,7 @@ def virtual_cube_matmul(form, A, B, C, A_pieces, B_pieces, C_pieces, scale_a=1.0
                                       _ptr(A_pieces), _ptr(B_pieces), _ptr(C_pieces), _stream(stream)),
            "virtual_cube_matmul")
     return C_pieces
+
+
+def cube3d_init() -> None:
+    _check(load().cube3d_init(), "cube3d_init")

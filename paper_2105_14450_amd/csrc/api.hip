@@ -577,6 +577,13 @@ int cube3d_activation_bwd(int kind, int z_dtype, int dh_dtype, int dz_dtype, int
     return activation_bwd(kind, z_dtype, dh_dtype, dz_dtype, n, z, dh, dz, static_cast<hipStream_t>(stream));
 }
 
+int cube3d_init(void)
+{
+    if (current_device() < 0) return CUBE3D_ELAUNCH;
+    (void)num_compute_units();
+    return setup_all_kernels();
+}
+
 const char *cube3d_status_string(int status)
 {
     switch (status) {

@@ -4,9 +4,25 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "cube3d.h"
 
 namespace cube3d {
+
+// ---- per-device facts and one-time set-up (device.hip) --------------------------------------------------
+constexpr int MAX_DEVICES = 64;     // device ordinals the per-device tables cover
+constexpr int DEFAULT_CUS = 256;    // MI355X; used only where no device can be queried (host-only checks)
+// Ordinal of the calling thread's current device, or -1 when there is none.
+int current_device();
+// Compute units of the current device (cached per device).
+int num_compute_units();
+// A kernel instantiation's one-time set-up on the current device (raises its dynamic LDS limit);
+// idempotent and thread-safe, returns a cube3d_status.  Every instantiation of the tuned product
+// kernel registers one, so that cube3d_init() can do all of them ahead of the first launch.
+typedef int (*KernelSetup)();
+std::vector<KernelSetup> &kernel_setups();
+int setup_all_kernels();
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));

@@ -8,8 +8,6 @@ using namespace mfk;
 
 namespace {
 
-constexpr int NUM_CU = 256;
-
 struct Plan {
     int tile;     // 256 or 128 (square output tile); 0 = shape not supported by the tuned kernel
     int splits;
@@ -31,6 +29,7 @@ bool map_ok(const AxisMap &m, int64_t extent, int64_t stride_align, bool contigu
 Plan make_plan(const GemmArgs &g)
 {
     Plan p{0, 1};
+    const int NUM_CU = num_compute_units();
     const bool fp8 = g.in_dtype == CUBE3D_FP8_E4M3;
     if (g.in_dtype != CUBE3D_BF16 && !fp8) return p;
     const int es = fp8 ? 1 : 2;

@@ -31,6 +31,8 @@
 // pointer per operand advanced once per K-tile plus lane-constant offsets, and the reads and
 // loads of a k-step are dealt out one per gap.
 #pragma once
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -845,25 +847,56 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     }
 }
 
+// LDS bytes of one configuration: the stage buffers; the large tiles add the epilogue staging (and
+// the bias strip) behind them.
+template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM> constexpr int cfg_lds_bytes()
+{
+    using ATile = typename std::conditional<AK, KMajorTile<E, BM, BKB>, MNMajorTile<E, BM, BKB>>::type;
+    using BTile = typename std::conditional<BKM, KMajorTile<E, BN, BKB>, MNMajorTile<E, BN, BKB>>::type;
+    return NSTAGE * (ATile::BYTES + BTile::BYTES) + (BM * BN > 128 * 128 ? 32 * 1024 : 0);
+}
+
+// One-time set-up of a configuration on the current device: the kernel needs more dynamic LDS than
+// the default limit.  Done once per device, under a lock (the flags are the only state the product
+// kernels keep); registered with kernel_setups() so that cube3d_init() can run it before the first
+// launch (a first launch from inside a stream capture would otherwise do it there).
+template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut, bool MAPPED> struct CfgSetup {
+    static int run()
+    {
+        static std::mutex mu;
+        static std::atomic<uint64_t> done{0};
+        const int dev = current_device();
+        if (dev < 0 || dev >= MAX_DEVICES) return CUBE3D_ELAUNCH;
+        const uint64_t bit = 1ull << dev;
+        if (done.load(std::memory_order_acquire) & bit) return CUBE3D_OK;
+        std::lock_guard<std::mutex> lock(mu);
+        if (done.load(std::memory_order_relaxed) & bit) return CUBE3D_OK;
+        auto kern = gemm_mfma_kernel<E, BM, BN, BKB, NSTAGE, AK, BKM, TOut, MAPPED>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                cfg_lds_bytes<E, BM, BN, BKB, NSTAGE, AK, BKM>()) != hipSuccess) {
+            (void)hipGetLastError();
+            return CUBE3D_ELAUNCH;
+        }
+        done.fetch_or(bit, std::memory_order_release);
+        return CUBE3D_OK;
+    }
+    struct Registrar {
+        Registrar() { kernel_setups().push_back(&run); }
+    };
+    static inline Registrar registrar;
+};
+
 // Launch one configuration.  splits > 1: every split writes its own fp32 partial result
 // [batch][split][Mo][No] to `out` (then out_ld = No); splits == 1: `out` is the final C.
 template <typename E, int BM, int BN, int BKB, int NSTAGE, bool AK, bool BKM, typename TOut, bool MAPPED = false>
 int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t out_batch_stride, int64_t out_split_stride,
                float alpha)
 {
-    using ATile = typename std::conditional<AK, KMajorTile<E, BM, BKB>, MNMajorTile<E, BM, BKB>>::type;
-    using BTile = typename std::conditional<BKM, KMajorTile<E, BN, BKB>, MNMajorTile<E, BN, BKB>>::type;
-    constexpr bool BIG = BM * BN > 128 * 128;
-    // stage buffers; the large tiles add the epilogue staging (and the bias strip) behind them
-    constexpr int LDS = NSTAGE * (ATile::BYTES + BTile::BYTES) + (BIG ? 32 * 1024 : 0);
+    constexpr int LDS = cfg_lds_bytes<E, BM, BN, BKB, NSTAGE, AK, BKM>();
+    using Setup = CfgSetup<E, BM, BN, BKB, NSTAGE, AK, BKM, TOut, MAPPED>;
+    (void)&Setup::registrar;   // instantiates the registration
     auto kern = gemm_mfma_kernel<E, BM, BN, BKB, NSTAGE, AK, BKM, TOut, MAPPED>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS) !=
-            hipSuccess)
-            return CUBE3D_ELAUNCH;
-        configured = true;
-    }
+    if (const int rc = Setup::run(); rc != CUBE3D_OK) return rc;
     Params p;
     p.A = g.A;
     p.B = g.B;
@@ -884,10 +917,13 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
         p.kb = make_kwalk(g.maps->b_k, BKB / E::ELT);
     }
     p.y_items = g.batch * splits;
-    // persistent workgroups: as many as the chip holds at once (a multiple of 8), or one per item
+    // persistent workgroups: as many as the chip holds at once, or one per item.  The item -> XCD
+    // regrouping in the kernel needs a grid that is a multiple of 8 whenever a workgroup takes more
+    // than one item.
     const int64_t items = (int64_t)p.tiles_m * p.tiles_n * p.y_items;
-    const int64_t resident = 256 * (LDS > 80 * 1024 ? 1 : 2);   // workgroups the 160 KB of a CU's LDS hold
-    if (items >= (1ll << 31)) return CUBE3D_ENOTIMPL;
+    const int64_t per_cu = LDS > 80 * 1024 ? 1 : 2;   // workgroups the 160 KB of a CU's LDS hold
+    const int64_t resident = (int64_t)num_compute_units() * per_cu / 8 * 8;
+    if (items >= (1ll << 31) || resident < 8) return CUBE3D_ENOTIMPL;
     dim3 grid((unsigned)(items < resident ? items : resident), 1, 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), LDS, g.stream, p);
     return launch_status();
