@@ -51,7 +51,9 @@
  * device, guarded by locks (calls may come from several threads): the number
  * of compute units, read once from the device, and one flag per kernel
  * variant saying that its one-time set-up (raising the kernel's dynamic LDS
- * limit with hipFuncSetAttribute) has been done on that device.  A variant is
+ * limit with hipFuncSetAttribute) has been done on that device; and the
+ * device address of the built-in scratch buffer of
+ * cube3d_linear_bwd_dw_noalloc.  A variant is
  * set up on its first use, or all at once by cube3d_init(); call cube3d_init()
  * on each device before capturing calls into a HIP graph, so that no set-up
  * falls into the capture.
@@ -79,7 +81,8 @@ typedef enum cube3d_status {
     CUBE3D_EDTYPE = -3,     /* unsupported in/out dtype combination */
     CUBE3D_EWORKSPACE = -4, /* workspace smaller than cube3d_workspace_bytes() */
     CUBE3D_ELAUNCH = -5,    /* the HIP runtime refused a launch */
-    CUBE3D_ENOTIMPL = -6
+    CUBE3D_ENOTIMPL = -6,
+    CUBE3D_ESCRATCH = -7    /* cube3d_linear_bwd_dw_noalloc: the call needs more than the built-in scratch */
 } cube3d_status;
 
 typedef enum cube3d_dtype {
@@ -164,6 +167,25 @@ int cube3d_linear_bwd_dx(const cube3d_desc *desc, int i, int j, int l,
 int cube3d_linear_bwd_dw(const cube3d_desc *desc, int i, int j, int l,
                          const void *X_block, const void *dY_block, void *R,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * cube3d_linear_bwd_dw for callers that cannot allocate or pass device scratch: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * the workspace, same kernels, same result bits.  Where cube3d_linear_bwd_dw would need a
+ * workspace (split-K partial sums, see cube3d_workspace_bytes), this call uses a buffer of
+ * CUBE3D_NOALLOC_SCRATCH_BYTES that is built into the library's device code: each GPU the library
+ * runs on holds one such buffer from the first use of the library on it until the process ends.
+ * The call allocates nothing and frees nothing.  A shape whose plan needs more scratch than that
+ * is refused with CUBE3D_ESCRATCH before anything is enqueued (use cube3d_linear_bwd_dw with a
+ * workspace for it).  All calls on one GPU share the one buffer: calls that may run at the same
+ * time on one GPU (different streams, or several threads) race on it and must be serialised by
+ * the caller.  Nothing in the buffer has to start at zero (every partial sum is written before it
+ * is read), so it is never cleared and keeps the last call's contents.  The buffer's address is
+ * looked up on the call's first use on a device, or by cube3d_init().
+ */
+#define CUBE3D_NOALLOC_SCRATCH_BYTES (16u << 20)
+int cube3d_linear_bwd_dw_noalloc(const cube3d_desc *desc, int i, int j, int l,
+                                 const void *X_block, const void *dY_block, void *R, void *stream);
 
 /* Scratch needed by a product call or by virtual_cube_bias_bwd.  op is a cube3d_op;
  * batched != 0 asks for the all-processors launch (ignored for CUBE3D_OP_BIAS_BWD, which

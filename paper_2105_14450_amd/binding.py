@@ -11,7 +11,8 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcube3d.so")
 
-OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH, ENOTIMPL = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ESHAPE, EDTYPE, EWORKSPACE, ELAUNCH, ENOTIMPL, ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7
+NOALLOC_SCRATCH_BYTES = 16 << 20
 F32, BF16, FP8_E4M3 = 0, 1, 2
 AXIS_X, AXIS_Y, AXIS_Z = 0, 1, 2
 OPERAND_X, OPERAND_W, OPERAND_DY, OPERAND_Y, OPERAND_DX, OPERAND_DW, OPERAND_BIAS = range(7)
@@ -134,6 +135,8 @@ def load():
     lib.cube3d_status_string.argtypes = [ci]
     lib.cube3d_status_string.restype = ctypes.c_char_p
     lib.cube3d_version.restype = ci
+    lib.cube3d_linear_bwd_dw_noalloc.argtypes = [dp, ci, ci, ci, vp, vp, vp, vp]
+    lib.cube3d_linear_bwd_dw_noalloc.restype = ci
     lib.cube3d_init.argtypes = []
     lib.cube3d_init.restype = ci
     _lib = lib
@@ -147,7 +150,7 @@ EXPORTS = ("cube3d_linear_fwd", "cube3d_linear_bwd_dx", "cube3d_linear_bwd_dw", 
            "virtual_cube_linear_bwd_dw", "virtual_cube_matrix_scatter", "virtual_cube_matrix_assemble",
            "virtual_cube_matrix_gather", "virtual_cube_matrix_reduce_scatter", "cube3d_matmul_workspace_bytes",
            "cube3d_matmul_blocks", "virtual_cube_matmul", "cube3d_activation_fwd", "cube3d_activation_bwd", "cube3d_status_string",
-           "cube3d_version", "cube3d_init")
+           "cube3d_version", "cube3d_init", "cube3d_linear_bwd_dw_noalloc")
 
 
 def status_string(status: int) -> str:
@@ -321,3 +324,10 @@ def virtual_cube_matmul(form, A, B, C, A_pieces, B_pieces, C_pieces, scale_a=1.0
 
 def cube3d_init() -> None:
     _check(load().cube3d_init(), "cube3d_init")
+
+
+def cube3d_linear_bwd_dw_noalloc(desc, rank, X_block, dY_block, R, stream=None):
+    i, j, l = rank
+    _check(load().cube3d_linear_bwd_dw_noalloc(ctypes.byref(desc), i, j, l, _ptr(X_block), _ptr(dY_block), _ptr(R),
+                                               _stream(stream)), "cube3d_linear_bwd_dw_noalloc")
+    return R

@@ -1,5 +1,7 @@
 // C-ABI entry points: argument validation on the host, then dispatch to the
 // kernels.  Nothing here touches the device before every check has passed.
+#include <mutex>
+
 #include "common.h"
 
 using namespace cube3d;
@@ -191,6 +193,32 @@ int run_cube_product(const cube3d_desc *d, int op, const void *A, const void *B,
     rc = gemm_fast(a);
     if (rc != CUBE3D_ENOTIMPL) return rc;
     return gemm_generic(a);
+}
+
+// ---- built-in scratch of the entry point that may not allocate --------------------------------------------
+// Device memory that is part of the loaded code object: every GPU the library runs on holds its own
+// copy, at its own address, until the process ends.  In host code the array's name only stands for
+// the symbol; the device address comes from hipGetSymbolAddress, once per device, and only that
+// address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[CUBE3D_NOALLOC_SCRATCH_BYTES];
+
+int scratch_address(void **out)
+{
+    static std::mutex mu;
+    static void *address[MAX_DEVICES] = {};
+    const int dev = current_device();
+    if (dev < 0 || dev >= MAX_DEVICES) return CUBE3D_ELAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (address[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return CUBE3D_ELAUNCH;
+        }
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return CUBE3D_OK;
 }
 
 }  // namespace
@@ -581,7 +609,30 @@ int cube3d_init(void)
 {
     if (current_device() < 0) return CUBE3D_ELAUNCH;
     (void)num_compute_units();
+    void *ws;
+    const int rc = scratch_address(&ws);
+    if (rc != CUBE3D_OK) return rc;
     return setup_all_kernels();
+}
+
+int cube3d_linear_bwd_dw_noalloc(const cube3d_desc *desc, int i, int j, int l, const void *X_block, const void *dY_block,
+                                 void *R, void *stream)
+{
+    int rc = check_desc(desc, nullptr);
+    if (rc != CUBE3D_OK) return rc;
+    const int batch = check_coords(desc, i, j, l);
+    if (batch < 0) return batch;
+    GemmArgs a;
+    rc = build_gemm(desc, CUBE3D_OP_BWD_DW, batch, X_block, dY_block, R, nullptr, 0, stream, &a);
+    if (rc != CUBE3D_OK) return rc;
+    const size_t need = workspace_for(a);
+    if (need > CUBE3D_NOALLOC_SCRATCH_BYTES) return CUBE3D_ESCRATCH;
+    void *ws = nullptr;
+    if (need > 0) {
+        rc = scratch_address(&ws);
+        if (rc != CUBE3D_OK) return rc;
+    }
+    return run_product(desc, CUBE3D_OP_BWD_DW, i, j, l, X_block, dY_block, R, ws, need, stream);
 }
 
 const char *cube3d_status_string(int status)
@@ -594,6 +645,7 @@ const char *cube3d_status_string(int status)
     case CUBE3D_EWORKSPACE: return "workspace too small";
     case CUBE3D_ELAUNCH: return "HIP launch failed";
     case CUBE3D_ENOTIMPL: return "not implemented";
+    case CUBE3D_ESCRATCH: return "the call needs more scratch memory than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }

@@ -243,7 +243,7 @@ def test_workspace_query_and_strings(lib):
     assert c3.cube3d_workspace_bytes(good(), 42, False) == 0
     assert isinstance(c3.cube3d_workspace_bytes(good(), c3.OP_FWD, True), int)
     seen = set()
-    for code in (c3.OK, c3.EINVAL, c3.ESHAPE, c3.EDTYPE, c3.EWORKSPACE, c3.ELAUNCH, c3.ENOTIMPL, -99):
+    for code in (c3.OK, c3.EINVAL, c3.ESHAPE, c3.EDTYPE, c3.EWORKSPACE, c3.ELAUNCH, c3.ENOTIMPL, c3.ESCRATCH, -99):
         s = c3.status_string(code)
         assert s and s not in seen
         seen.add(s)
@@ -264,6 +264,24 @@ def test_workspace_too_small_is_reported_before_any_launch(lib):
     big = c3.make_desc(4, 32768, 8192, 32768, in_dtype=c3.BF16, out_dtype=c3.BF16)
     for op in (c3.OP_FWD, c3.OP_BWD_DX, c3.OP_BWD_DW):
         assert c3.cube3d_workspace_bytes(big, op, False) == 0
+
+
+def test_noalloc_entry_point_argument_errors(lib):
+    def na(d, rank=(0, 0, 0), a=FAKE, b=FAKE, c=FAKE):
+        dp = ctypes.byref(d) if d is not None else None
+        return lib.cube3d_linear_bwd_dw_noalloc(dp, rank[0], rank[1], rank[2], a, b, c, None)
+    assert na(None) == c3.EINVAL
+    assert na(good(M=258)) == c3.ESHAPE
+    assert na(good(in_dtype=9)) == c3.EDTYPE
+    assert na(good(), rank=(2, 0, 0)) == c3.EINVAL
+    assert na(good(), a=None) == c3.EINVAL
+    assert na(good(), c=ODD) == c3.EINVAL
+    # a plan with more split-K partial sums than the built-in scratch buffer holds is refused
+    big = c3.make_desc(4, 4 * 65536, 4 * 768, 4 * 2048, in_dtype=c3.BF16, out_dtype=c3.BF16)
+    assert c3.cube3d_workspace_bytes(big, c3.OP_BWD_DW, False) > c3.binding.NOALLOC_SCRATCH_BYTES
+    assert na(big) == c3.ESCRATCH
+    header = open(os.path.join(ROOT, "include", "cube3d.h")).read()
+    assert "#define CUBE3D_NOALLOC_SCRATCH_BYTES (16u << 20)" in header and c3.binding.NOALLOC_SCRATCH_BYTES == 16 << 20
 
 
 def test_binding_refuses_host_tensors():
