@@ -46,6 +46,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="config4", choices=sorted(RANK_SHARE))
+    ap.add_argument("--dist", default="normal", choices=["normal", "uniform", "zeros"],
+                    help="operand distribution of the headline workload: the configuration's own (N(0,1) activations and "
+                         "gradients, N(0,0.02) weights), uniform[-1,1), or all zeros (the achieved rate depends on the data: "
+                         "the shader clock under the matrix cores does)")
+    ap.add_argument("--repeats", type=int, default=5, help="measurements per reported figure (the median is reported)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time aimed at by the cpu_baseline sample")
@@ -54,6 +59,24 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for scaling profiler byte counters)")
     return ap.parse_args()
+
+
+def csrc_digest():
+    """Digest of the kernel sources: ties a stored profiler figure to the code it was measured on."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2105_14450_amd", "csrc", "*")) +
+                       glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
 def main():
@@ -76,7 +99,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
+    c3.cube3d_init()
     stream = torch.cuda.current_stream()
+    REP = max(1, args.repeats)
 
     store = {"f32": torch.float32, "bf16": torch.int16, "fp8_e4m3": torch.uint8}
 
@@ -86,16 +111,21 @@ def main():
             raw = raw.view(np.int16)
         return torch.from_numpy(raw).cuda()
 
-    def timed(fn, iters):
-        """Average milliseconds of fn() over `iters` back-to-back calls (HIP events on the launch stream)."""
+    def timed_once(fn, iters):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
         e0.record(stream)
         for _ in range(iters):
             fn()
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
+
+    def timed(fn, iters):
+        """Milliseconds per call of fn(): `iters` back-to-back calls between two HIP events on the launch
+        stream, median of REP such measurements."""
+        fn()
+        torch.cuda.synchronize()
+        return median([timed_once(fn, iters) for _ in range(REP)])
 
     def timed_graph(fn, iters):
         """Same, with the `iters` launches replayed from one HIP graph (no host launch gaps)."""
@@ -109,46 +139,56 @@ def main():
                     fn()
         g.replay()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        g.replay()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        return median([timed_once(g.replay, 1) for _ in range(REP)]) / iters
 
-    def rank_share(name, seed):
+    def rank_share(name, seed, dist="normal", copies=1):
+        """One processor's three products of a configuration.  copies > 1: that many separate sets of
+        operand and result buffers (same values), for launches that never find their data in a cache."""
         q, M, K, N, dt, odt, desc = RANK_SHARE[name]
         Mb, Kb, Nb = M // q, K // q, N // q
-        X = synth.store(synth.draw((Mb, Kb), "normal", seed, synth.TID_X), dt)
-        W = synth.store(synth.draw((Kb, Nb), "normal", seed, synth.TID_W, 0.02), dt)
-        G = synth.store(synth.draw((Mb, Nb), "normal", seed, synth.TID_DY), dt)
+        if dist == "zeros":
+            z = lambda shape: synth.store(np.zeros(shape, dtype=np.float32), dt, True)
+            X, W, G = z((Mb, Kb)), z((Kb, Nb)), z((Mb, Nb))
+        else:
+            sw = 0.02 if dist == "normal" else 1.0
+            X = synth.store(synth.draw((Mb, Kb), dist, seed, synth.TID_X), dt)
+            W = synth.store(synth.draw((Kb, Nb), dist, seed, synth.TID_W, sw), dt)
+            G = synth.store(synth.draw((Mb, Nb), dist, seed, synth.TID_DY), dt)
         d = c3.make_desc(q, M, K, N, in_dtype=c3.binding.DTYPE_CODES[dt], out_dtype=c3.binding.DTYPE_CODES[odt],
                          scale_x=X[1], scale_w=W[1], scale_dy=G[1])
-        t = {"X": dev(X[0]), "W": dev(W[0]), "G": dev(G[0]),
-             "P": torch.empty((Mb, Nb), dtype=store[odt], device="cuda"),
-             "Q": torch.empty((Mb, Kb), dtype=store[odt], device="cuda"),
-             "R": torch.empty((Kb, Nb), dtype=store[odt], device="cuda")}
+        sets = []
+        for _ in range(copies):
+            sets.append({"X": dev(X[0]), "W": dev(W[0]), "G": dev(G[0]),
+                         "P": torch.empty((Mb, Nb), dtype=store[odt], device="cuda"),
+                         "Q": torch.empty((Mb, Kb), dtype=store[odt], device="cuda"),
+                         "R": torch.empty((Kb, Nb), dtype=store[odt], device="cuda")})
         ws = {}
         for op in (c3.OP_FWD, c3.OP_BWD_DX, c3.OP_BWD_DW):
             n = c3.cube3d_workspace_bytes(d, op, False)
             ws[op] = torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
         rank = (1, 2, 3)
-        ops = {
-            "fwd": lambda: c3.cube3d_linear_fwd(d, rank, t["X"], t["W"], t["P"], ws[c3.OP_FWD]),
-            "bwd_dx": lambda: c3.cube3d_linear_bwd_dx(d, rank, t["G"], t["W"], t["Q"], ws[c3.OP_BWD_DX]),
-            "bwd_dw": lambda: c3.cube3d_linear_bwd_dw(d, rank, t["X"], t["G"], t["R"], ws[c3.OP_BWD_DW]),
-        }
+
+        def make(t):
+            return {
+                "fwd": lambda: c3.cube3d_linear_fwd(d, rank, t["X"], t["W"], t["P"], ws[c3.OP_FWD]),
+                "bwd_dx": lambda: c3.cube3d_linear_bwd_dx(d, rank, t["G"], t["W"], t["Q"], ws[c3.OP_BWD_DX]),
+                "bwd_dw": lambda: c3.cube3d_linear_bwd_dw(d, rank, t["X"], t["G"], t["R"], ws[c3.OP_BWD_DW]),
+            }
+        ops = [make(t) for t in sets]
         flop = 2.0 * Mb * Kb * Nb
         host = {"X": X, "W": W, "G": G}
-        return ops, flop, (Mb, Kb, Nb), desc, dt, host
+        set_bytes = sum(v.numel() * v.element_size() for v in sets[0].values())
+        return (ops[0] if copies == 1 else ops), flop, (Mb, Kb, Nb), desc, dt, host, set_bytes
+
+    ORDER = ("fwd", "bwd_dx", "bwd_dw")
+    SEEDS = {"config2": 2, "config4": 4, "config5": 5}
 
     # ---- headline workload ------------------------------------------------------------------------
-    ops, flop, (Mb, Kb, Nb), desc, dt, host = rank_share(args.workload, {"config2": 2, "config4": 4, "config5": 5}[args.workload])
+    ops, flop, (Mb, Kb, Nb), desc, dt, host, _ = rank_share(args.workload, SEEDS[args.workload], args.dist)
 
     def step():
-        ops["fwd"]()
-        ops["bwd_dx"]()
-        ops["bwd_dw"]()
+        for k in ORDER:
+            ops[k]()
 
     for _ in range(args.warmup):
         step()
@@ -162,24 +202,52 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     value = 3.0 * flop / (ms_per_step * 1e-3) / 1e12
 
-    # per-kernel launch durations, measured live (same stream, HIP events)
+    # Per-kernel launch durations, measured live IN STEP ORDER: an event behind every launch of REP more
+    # passes of `steps` steps, so each kernel finds the caches as the step leaves them (a loop over one
+    # product alone keeps its whole working set in the 256 MB Infinity Cache and reads faster than it
+    # runs inside the step).  Duration of a launch = time between the events around it on the launch
+    # stream; reported: the median over all REP * steps launches of that kernel.
+    per = {k: [] for k in ORDER}
+    step_ms = []
+    for _ in range(REP):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(ORDER) + 1)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for row in evs:
+            row[0].record(stream)
+            for j, k in enumerate(ORDER):
+                ops[k]()
+                row[j + 1].record(stream)
+        torch.cuda.synchronize()
+        for row in evs:
+            for j, k in enumerate(ORDER):
+                per[k].append(row[j].elapsed_time(row[j + 1]))
+        step_ms.append(evs[0][0].elapsed_time(evs[-1][-1]) / args.steps)
     kern = {}
-    small = flop < 5e10
-    for name, fn in ops.items():
-        ms = timed_graph(fn, 50) if small else timed(fn, max(20, args.steps // 4))
-        kern[name] = {"avg_us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
-                      "frac_of_peak": round(flop / (ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 4)}
+    for k in ORDER:
+        ms = median(per[k])
+        kern[k] = {"avg_us": round(ms * 1e3, 2), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
+                   "frac_of_peak": round(flop / (ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt], 4)}
     dom = max(kern, key=lambda k: kern[k]["avg_us"])
-    traffic = None
+    # HBM traffic of the dominant kernel from the stored profiler counters, only if they were measured
+    # on these very kernel sources and this operand distribution
+    traffic, traffic_note = None, "no stored counters"
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(dom)
-        except Exception:
-            traffic = None
+            tj = json.load(open(tpath))
+            if tj.get("csrc_digest") != csrc_digest():
+                traffic_note = "stored counters are from other kernel sources (digest %s)" % tj.get("csrc_digest")
+            elif args.dist != "normal":
+                traffic_note = "stored counters are for the configuration's own operand distribution"
+            else:
+                traffic = tj["bytes_per_launch"].get(dom)
+                traffic_note = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, measured at source digest %s" % tj["csrc_digest"]
+        except Exception as exc:
+            traffic_note = "unreadable: %r" % (exc,)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": kern[dom]["tflops"], "peak": PEAK_TFLOPS[dt],
-                "unit": "TFLOP/s", "frac": kern[dom]["frac_of_peak"], "traffic": traffic,
-                "flop_per_launch": flop, "avg_launch_us": kern[dom]["avg_us"]}
+                "unit": "TFLOP/s", "frac": kern[dom]["frac_of_peak"], "traffic": traffic, "traffic_note": traffic_note,
+                "flop_per_launch": flop, "avg_launch_us": kern[dom]["avg_us"],
+                "timing": "median of %d launches timed in step order by HIP events" % len(per[dom])}
 
     out = {
         "metric": "per-rank 3-D linear fwd+bwd TFLOP/s (bf16)" if dt == "bf16" else
@@ -187,8 +255,9 @@ def main():
         "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"bf16": "bf16", "fp8_e4m3": "fp8", "f32": "f32"}[dt], "data": "synthetic",
-        "config": {"workload": args.workload + ": " + desc, "rank_block": [Mb, Kb, Nb],
-                   "step": "fwd + bwd_dx + bwd_dw, 3 launches", "frac_of_bf16_peak": round(value / PEAK_TFLOPS["bf16"], 4)},
+        "config": {"workload": args.workload + ": " + desc, "rank_block": [Mb, Kb, Nb], "operands": args.dist,
+                   "step": "fwd + bwd_dx + bwd_dw, 3 launches", "frac_of_bf16_peak": round(value / PEAK_TFLOPS["bf16"], 4),
+                   "ms_per_step_repeats": [round(v, 4) for v in step_ms], "csrc_digest": csrc_digest()},
         "roofline": roofline,
         "kernels": kern,
     }
@@ -207,16 +276,7 @@ def main():
             if name == args.workload:
                 continue
             try:
-                o, f, blk, _, d2, _h = rank_share(name, {"config2": 2, "config4": 4, "config5": 5}[name])
-                r = {}
-                for k, fn in o.items():
-                    ms = timed_graph(fn, 50) if f < 5e10 else timed(fn, 20)
-                    r[k] = {"avg_us": round(ms * 1e3, 2), "tflops": round(f / (ms * 1e-3) / 1e12, 1)}
-                r["fwd_bwd_tflops"] = round(3 * f / sum(v["avg_us"] for v in r.values()) / 1e6, 1)
-                r["frac_of_bf16_peak"] = round(r["fwd_bwd_tflops"] / PEAK_TFLOPS["bf16"], 4)
-                r["dtype"] = d2
-                extra[name] = r
-                del o, _h
+                extra[name] = bench_small_config(name, SEEDS[name], rank_share, timed, timed_graph, timed_once, torch, REP)
                 torch.cuda.empty_cache()
             except Exception as exc:   # a failed side run must not lose the headline line
                 extra[name] = {"error": repr(exc)}
@@ -226,7 +286,7 @@ def main():
             extra["config3"] = {"error": repr(exc)}
         if args.config3_linear is None:
             try:
-                extra["config3"]["layer_chain"] = bench_layer_chain(c3, torch, stream)
+                extra["config3"]["layer_chain"] = bench_layer_chain(c3, torch, stream, REP)
             except Exception as exc:
                 extra["config3"]["layer_chain"] = {"error": repr(exc)}
         out["per_config"] = extra
@@ -237,6 +297,40 @@ def main():
 
     print(json.dumps(out))
     return 0
+
+
+def bench_small_config(name, seed, rank_share, timed, timed_graph, timed_once, torch, REP):
+    """A configuration whose launches may be shorter than 20 us: per product the graph-replayed time on
+    one set of buffers (which then sits in the caches: `avg_us`), and a cold figure (`cold_us`): the same
+    launches replayed from a graph that walks through enough separate buffer sets (> 512 MB in all, twice
+    the Infinity Cache) that no launch finds its operands in a cache."""
+    o, f, blk, _, d2, _h, set_bytes = rank_share(name, seed)
+    r = {}
+    small = f < 5e10
+    for k, fn in o.items():
+        ms = timed_graph(fn, 50) if small else timed(fn, 20)
+        r[k] = {"avg_us": round(ms * 1e3, 2), "tflops": round(f / (ms * 1e-3) / 1e12, 1)}
+    r["fwd_bwd_tflops"] = round(3 * f / sum(v["avg_us"] for v in r.values()) / 1e6, 1)
+    r["frac_of_bf16_peak"] = round(r["fwd_bwd_tflops"] / PEAK_TFLOPS["bf16"], 4)
+    r["frac_of_own_peak"] = round(r["fwd_bwd_tflops"] / PEAK_TFLOPS[d2], 4)
+    r["dtype"] = d2
+    r["timing"] = "median of %d graph replays of 50 launches each" % REP if small else "median of %d loops of 20 launches" % REP
+    del o
+    if small:
+        copies = int((512 << 20) // set_bytes) + 2
+        sets, f, _, _, _, _, _ = rank_share(name, seed, copies=copies)
+        cold = {}
+        for k in ("fwd", "bwd_dx", "bwd_dw"):
+            def walk(k=k):
+                for ops in sets:
+                    ops[k]()
+            ms = timed_graph(walk, 1) / copies
+            cold[k] = round(ms * 1e3, 2)
+        r["cold_us"] = cold
+        r["cold_fwd_bwd_tflops"] = round(3 * f / sum(cold.values()) / 1e6, 1)
+        r["cold_buffer_sets"] = copies
+        del sets
+    return r
 
 
 def bench_virtual_cube(c3, synth, torch, np, timed, only=None):
@@ -353,7 +447,7 @@ def bench_virtual_cube(c3, synth, torch, np, timed, only=None):
     return res
 
 
-def bench_layer_chain(c3, torch, stream):
+def bench_layer_chain(c3, torch, stream, REP=5):
     """The four linears of config 3 as one chained layer step on the 64-processor virtual cube, forward and
     backward, in-place cube products with bias, the direction exchange between consecutive linears
     (y, z, y, z) and the activation between the two MLP linears: timed eagerly and as one captured graph."""
@@ -399,14 +493,17 @@ def bench_layer_chain(c3, torch, stream):
         bwd(L["qkv"], L["qkv"]["dy"])
 
     def timed(run, iters):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record(stream)
-        for _ in range(iters):
-            run()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        vals = []
+        for _ in range(REP):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(iters):
+                run()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            vals.append(e0.elapsed_time(e1) / iters)
+        return median(vals)
 
     step()
     step()

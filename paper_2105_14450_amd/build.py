@@ -14,7 +14,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-inline-asm"]
+         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-inline-asm"] + \
+    os.environ.get("CUBE3D_EXTRA_FLAGS", "").split()
 
 
 SCRATCH_LIMIT = 1024   # bytes per lane
@@ -101,6 +102,29 @@ def build(force: bool = True, jobs: int = 8) -> str:
                     "-Wl,-rpath,/opt/rocm/lib"], check=True)
     os.replace(tmp, LIB)
     return LIB
+
+
+def build_sanitized(outdir: str, jobs: int = 8) -> str:
+    """The library with its HOST code under AddressSanitizer and UndefinedBehaviorSanitizer (the device
+    code is compiled as usual), for the host-only check of the argument-validation layer.  Returns the
+    path of ``libcube3d_san.so`` in `outdir`."""
+    os.makedirs(outdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+    def one(src):
+        obj = os.path.join(outdir, os.path.basename(src) + ".o")
+        res = subprocess.run([HIPCC, *FLAGS, *san, "-c", src, "-o", obj], stderr=subprocess.PIPE, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stderr)
+            raise subprocess.CalledProcessError(res.returncode, HIPCC)
+        return obj
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(one, sources()))
+    lib = os.path.join(outdir, "libcube3d_san.so")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-fno-gpu-sanitize", "-o", lib, *objs, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    return lib
 
 
 if __name__ == "__main__":

@@ -796,7 +796,10 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     if constexpr (!MAPPED)
                         gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * row_stride + jh * JH * 32) + (lane % LPR) * 16;
                     else gp = reinterpret_cast<char *>(C + col + strip_m + (int64_t)row * row_stride);
-                    *reinterpret_cast<i32x4 *>(gp) = v;
+                    // streaming store: the product is not read again by this kernel, and kept out of the
+                    // caches it leaves them to the operand panels that other XCDs still fetch (measured
+                    // on the large bf16 shapes, three products back to back: +1.4 %, dX +3.8 %)
+                    __builtin_nontemporal_store(v, reinterpret_cast<i32x4 *>(gp));
                 }
                 // one strip at a time: without this the scheduler pulls all accumulator reads to the
                 // front and needs a register for every output element at once
