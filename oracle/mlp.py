@@ -22,7 +22,16 @@ import numpy as np
 from . import matmul as _mm
 
 KINDS = ("relu", "gelu")
-_erf = np.vectorize(math.erf, otypes=[np.float64])
+
+# The error function is a library primitive here: scipy's vectorised fp64 erf where scipy is
+# importable (the full-size cases have 67 million pre-activations), else the C library's through
+# Python's math module, element by element.  The two agree to the last bit or two in fp64; the
+# tests pin whichever is in use against tabulated values of the normal distribution function.
+try:
+    from scipy.special import erf as _erf
+except ImportError:                      # pragma: no cover
+    _erf = np.vectorize(math.erf, otypes=[np.float64])
+_erf_scalar = np.vectorize(math.erf, otypes=[np.float64])
 
 
 def _phi_cdf(z):
@@ -57,22 +66,22 @@ def _same(x):
     return x
 
 
-def forward(X, W1, b1, W2, b2, kind, store_z=_same, store_h=_same, store_y=_same):
-    """Returns (Z, H, Y) as the device stores them."""
-    Z = store_z(_mm.forward(X, W1) + np.asarray(b1, dtype=np.float64)[None, :])
+def forward(X, W1, b1, W2, b2, kind, store_z=_same, store_h=_same, store_y=_same, threads=1):
+    """Returns (Z, H, Y) as the device stores them.  `threads`: host threads of the plain products."""
+    Z = store_z(_mm.forward(X, W1, threads) + np.asarray(b1, dtype=np.float64)[None, :])
     H = store_h(act(Z, kind))
-    Y = store_y(_mm.forward(H, W2) + np.asarray(b2, dtype=np.float64)[None, :])
+    Y = store_y(_mm.forward(H, W2, threads) + np.asarray(b2, dtype=np.float64)[None, :])
     return Z, H, Y
 
 
-def backward(dY, X, W1, Z, H, W2, kind, store_g=_same, store_dz=_same):
+def backward(dY, X, W1, Z, H, W2, kind, store_g=_same, store_dz=_same, threads=1):
     """Gradients of <dY, Y>: returns dict with dX, dW1, db1, dW2, db2 (and dH, dZ as stored)."""
     dY = np.asarray(dY, dtype=np.float64)
-    dH = store_g(_mm.backward_dx(dY, W2))                  # dH = dY W2^T
-    dW2 = _mm.backward_dw(H, dY)                           # dW2 = H^T dY
+    dH = store_g(_mm.backward_dx(dY, W2, threads))         # dH = dY W2^T
+    dW2 = _mm.backward_dw(H, dY, threads)                  # dW2 = H^T dY
     db2 = dY.sum(axis=0)
     dZ = store_dz(dH * act_grad(Z, kind))
-    dX = _mm.backward_dx(dZ, W1)
-    dW1 = _mm.backward_dw(X, dZ)
+    dX = _mm.backward_dx(dZ, W1, threads)
+    dW1 = _mm.backward_dw(X, dZ, threads)
     db1 = dZ.sum(axis=0)
     return {"dH": dH, "dZ": dZ, "dX": dX, "dW1": dW1, "db1": db1, "dW2": dW2, "db2": db2}

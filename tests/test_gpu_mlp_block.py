@@ -125,11 +125,12 @@ class Block:
         torch.cuda.synchronize()
         return {k: gu.to_host(v, "f32" if k.startswith("db") else dt) for k, v in out.items()}
 
-    def reference(self):
+    def reference(self, threads=4):
         st = _round(self.dtype)
         v = self.val
-        Z, H, Y = mlp.forward(v["X"], v["W1"], self.b1, v["W2"], self.b2, self.kind, store_z=st, store_h=st, store_y=st)
-        g = mlp.backward(v["dY"], v["X"], v["W1"], Z, H, v["W2"], self.kind, store_g=st, store_dz=st)
+        Z, H, Y = mlp.forward(v["X"], v["W1"], self.b1, v["W2"], self.b2, self.kind, store_z=st, store_h=st, store_y=st,
+                              threads=threads)
+        g = mlp.backward(v["dY"], v["X"], v["W1"], Z, H, v["W2"], self.kind, store_g=st, store_dz=st, threads=threads)
         g.update(Z=Z, H=H, Y=Y)
         return g
 
@@ -180,3 +181,70 @@ def test_mlp_block_in_a_graph_replays_bit_for_bit():
         got = blk.results()
         for k, v in eager.items():
             np.testing.assert_array_equal(got[k], v, err_msg="replay %d: %s" % (rep, k))
+
+
+# ---- the block at the size of the benchmark's layer: q = 4, 8192 tokens, 2048 -> 8192 -> 2048, bf16 ----------
+NAMES = ("Z", "H", "Y", "dH", "dZ", "dX", "dW1", "dW2", "db1", "db2")
+
+
+def _replay_and_compare(blk, eager, replays=2):
+    """The step captured in a HIP graph; every replay (outputs poisoned in between by eager work) must
+    give the eager run's bits."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            blk.step()
+    torch.cuda.synchronize()
+    for rep in range(replays):
+        for t in (blk.z, blk.h, blk.y, blk.dh, blk.dz, blk.dx, blk.dw1, blk.dw2, blk.db1, blk.db2):
+            t.view(torch.uint8).fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = blk.results()
+        for k, v in eager.items():
+            np.testing.assert_array_equal(got[k], v, err_msg="replay %d: %s" % (rep, k))
+
+
+def test_mlp_block_full_size_rectifier_integers_bit_exact():
+    """Integer data and the rectifier: every stored intermediate and gradient of the chain equals the
+    oracle's bit for bit (each stage: exact sum, one rounding to bf16), eagerly and replayed from a graph."""
+    from oracle import matmul as om
+    threads = min(16, om.max_threads())
+    blk = Block(4, 8192, 2048, 8192, 2048, "bf16", "int", 93, "relu")
+    print("mlp block full size: bf16 integers, rectifier", flush=True)
+    blk.step()
+    got, ref = blk.results(), blk.reference(threads)
+    # exactness of the fp32 accumulation in any order: the absolute terms of every sum stay below 2^24
+    # (checked on the longest contractions, whose operands are the rounded intermediates)
+    v = blk.val
+    for a, b in ((np.abs(ref["H"]), np.abs(v["W2"])), (np.abs(ref["dZ"]), np.abs(v["W1"]).T),
+                 (np.abs(v["X"]).T, np.abs(ref["dZ"])), (np.abs(ref["H"]).T, np.abs(v["dY"]))):
+        assert float(np.max(a.astype(np.float32) @ b.astype(np.float32))) < 2.0 ** 24
+    st = _round("bf16")
+    for name in NAMES:
+        # the oracle returns the parameter and input gradients unrounded; the device stores them in bf16
+        want = st(ref[name]) if name in ("dX", "dW1", "dW2") else ref[name]
+        np.testing.assert_array_equal(got[name], want, err_msg=name)
+    del ref
+    _replay_and_compare(blk, got)
+
+
+def test_mlp_block_full_size_gelu():
+    """N(0,1) activations, N(0,0.02) weights, GELU: every stage within one bf16 rounding of the oracle's
+    value computed from the same stored inputs of that stage's predecessors."""
+    from oracle import matmul as om
+    threads = min(16, om.max_threads())
+    blk = Block(4, 8192, 2048, 8192, 2048, "bf16", "normal", 94, "gelu")
+    print("mlp block full size: bf16 normal, GELU", flush=True)
+    blk.step()
+    got, ref = blk.results(), blk.reference(threads)
+    for name in NAMES:
+        err = gu.scaled_max_err(got[name], ref[name])
+        # a rounding of an intermediate that falls the other way on the two sides moves its consumers by
+        # less than their own rounding; the bias gradients are fp32 sums over 8192 such bf16 values
+        print("  %s: scaled max error %.3g" % (name, err), flush=True)
+        assert err <= (1e-3 if name.startswith("db") else 8e-3), (name, err)
+    del ref
+    _replay_and_compare(blk, got)

@@ -33,6 +33,12 @@ def test_tabulated_values_and_symmetry(golden_dir):
         mlp.act(z, "tanh")
 
 
+def test_the_two_error_function_routines_agree():
+    # the vectorised library routine the oracle uses against the C library's, on a fine grid
+    z = np.concatenate([np.linspace(-6, 6, 48001), [0.0, 1e-300, -1e-300, 30.0, -30.0]])
+    np.testing.assert_allclose(mlp._erf(z), mlp._erf_scalar(z), rtol=0, atol=1e-15)
+
+
 def test_slope_is_the_derivative():
     z = np.linspace(-5, 5, 101) + 0.013
     h = 1e-5
