@@ -4,9 +4,11 @@
 // All q^3 processors' buffers live in this GPU's memory, so every "collective"
 // is a streaming copy or a streaming sum: HBM-bandwidth work, no matrix cores.
 //
-// Work decomposition: blockIdx.z = destination processor r, blockIdx.x = a group
-// of destination rows; each wavefront takes whole rows, its lanes stride over
-// 16-byte pieces of the row.  All index decoding is wave-uniform.
+// Work decomposition.  Scatter / assemble and the reduce-scatters: blockIdx.z =
+// destination processor r, blockIdx.x = a group of destination rows; each
+// wavefront takes whole rows, its lanes stride over 16-byte pieces of the row; all
+// index decoding is wave-uniform.  All-gathers: blockIdx.z = SOURCE processor, whose
+// shard is read once and written to the q members of its group (cube_gather_kernel).
 #include "common.h"
 
 namespace cube3d {
@@ -191,6 +193,77 @@ __global__ __launch_bounds__(256) void cube_copy_kernel(CubeGeom g, int mode, in
     }
 }
 
+// All-gather, source-major: blockIdx.z = the SOURCE processor, whose shard (one contiguous array of
+// rows x seg elements) is read exactly once and written to the q processors of its group, each row
+// into its place in their gathered blocks.  (Destination-major, every shard would be fetched q times,
+// by workgroups on different XCDs.)  A lane has U 16-byte loads in flight before its U * q stores; the
+// stores are streaming stores (the gathered copies are not read again by this kernel).
+//   destination of (member d, shard row, vector c) = first + d * step + row * ld + c      (in VecT units)
+struct GatherMap {
+    int64_t rows, seg;            // shard rows, elements per shard row
+    int64_t first, step, ld;      // elements: offset for member 0, distance between members, destination row length
+};
+
+__device__ __forceinline__ GatherMap map_gather(const CubeGeom &g, int mode, int r)
+{
+    GatherMap m;
+    if (mode == MV_PLACE_GATHER) {
+        const PlaceCoords pc = decode_place(g, r);
+        const int64_t blk = g.pRb * g.pCb;
+        m.rows = g.pRs; m.seg = g.pCs;
+        m.first = (r - pc.s * pc.rstride) * blk + (g.p_split_rows ? (int64_t)pc.s * g.pRs * g.pCb : (int64_t)pc.s * g.pCs);
+        m.step = pc.rstride * blk;
+        m.ld = g.pCb;
+        return m;
+    }
+    const Coords c = decode_rank(g, r);
+    if (mode == MV_GATHER_X) {          // shard of (i, a', b): row panel a' of the blocks of (i, ., b)
+        m.rows = g.Ms; m.seg = g.Kb; m.ld = g.Kb;
+        m.first = rank_index(g, c.i, 0, c.b) * g.Mb * g.Kb + (int64_t)c.a * g.Ms * g.Kb;
+        m.step = (rank_index(g, c.i, 1 % g.q, c.b) - rank_index(g, c.i, 0, c.b)) * g.Mb * g.Kb;
+    } else if (mode == MV_GATHER_DY) {  // shard of (i, a, b'): row panel b' of the blocks of (i, a, .)
+        m.rows = g.Ms; m.seg = g.Nb; m.ld = g.Nb;
+        m.first = rank_index(g, c.i, c.a, 0) * g.Mb * g.Nb + (int64_t)c.b * g.Ms * g.Nb;
+        m.step = (rank_index(g, c.i, c.a, 1 % g.q) - rank_index(g, c.i, c.a, 0)) * g.Mb * g.Nb;
+    } else {                            // MV_GATHER_W: shard of (i', a, b): column panel i' of the blocks of (., a, b)
+        m.rows = g.Kb; m.seg = g.Ns; m.ld = g.Nb;
+        m.first = rank_index(g, 0, c.a, c.b) * g.Kb * g.Nb + (int64_t)c.i * g.Ns;
+        m.step = (rank_index(g, 1 % g.q, c.a, c.b) - rank_index(g, 0, c.a, c.b)) * g.Kb * g.Nb;
+    }
+    return m;
+}
+
+template <typename VecT, int U>
+__global__ __launch_bounds__(256) void cube_gather_kernel(CubeGeom g, int mode, int es, const char *__restrict__ src,
+                                                          char *__restrict__ dst)
+{
+    const int r = blockIdx.z;
+    const GatherMap m = map_gather(g, mode, r);
+    const int64_t vpr = m.seg * es / (int64_t)sizeof(VecT);          // vectors per shard row
+    const int64_t total = m.rows * vpr;                              // vectors in the shard
+    const int64_t ld = m.ld * es / (int64_t)sizeof(VecT), step = m.step * es / (int64_t)sizeof(VecT);
+    const VecT *s = reinterpret_cast<const VecT *>(src) + (int64_t)r * total;
+    VecT *d = reinterpret_cast<VecT *>(dst) + m.first * es / (int64_t)sizeof(VecT);
+    const int q = g.q;
+    const int64_t f0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x;
+    VecT v[U];
+    int64_t off[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t f = f0 + 256 * u;
+        if (f < total) {
+            v[u] = s[f];
+            const int64_t row = (uint64_t)(f | vpr) < (1ull << 32) ? (int64_t)((uint32_t)f / (uint32_t)vpr) : f / vpr;
+            off[u] = row * ld + (f - row * vpr);
+        }
+    }
+    for (int member = 0; member < q; ++member) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (f0 + 256 * u < total) __builtin_nontemporal_store(v[u], d + member * step + off[u]);
+    }
+}
+
 template <typename T> __device__ __forceinline__ float load_f32(const T *p);
 template <> __device__ __forceinline__ float load_f32<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float load_f32<unsigned short>(const unsigned short *p)
@@ -208,9 +281,31 @@ template <typename T, int V> struct __attribute__((aligned(sizeof(T) * V))) Pack
     T v[V];
 };
 
+// Streaming (non-temporal) access to a pack: data that is touched once should not displace what
+// other kernels left in the caches.  The builtins take scalars or vectors, so a pack travels as the
+// integer vector of its size.
+template <int BYTES> struct RawVec;
+template <> struct RawVec<16> { typedef i32x4 type; };
+template <> struct RawVec<8> { typedef int type __attribute__((ext_vector_type(2))); };
+template <> struct RawVec<4> { typedef int type; };
+template <> struct RawVec<2> { typedef short type; };
+
+template <typename P> __device__ __forceinline__ P stream_load_pack(const P *p)
+{
+    typedef typename RawVec<sizeof(P)>::type R;
+    return __builtin_bit_cast(P, __builtin_nontemporal_load(reinterpret_cast<const R *>(p)));
+}
+
+template <typename P> __device__ __forceinline__ void stream_store_pack(P *p, const P &v)
+{
+    typedef typename RawVec<sizeof(P)>::type R;
+    __builtin_nontemporal_store(__builtin_bit_cast(R, v), reinterpret_cast<R *>(p));
+}
+
 // Sum over the q partials of a reduce direction, fp32, ascending index, one rounding at the
 // store.  V elements per lane per step; the loads of up to four partials are in flight together.
-template <typename TIn, typename TOut, int V>
+// STREAM: streaming loads and stores, for partials that cannot stay in the caches anyway.
+template <typename TIn, typename TOut, int V, bool STREAM>
 __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, int64_t rows,
                                                           const TIn *__restrict__ partials, TOut *__restrict__ shards,
                                                           const float *__restrict__ bias)
@@ -260,7 +355,10 @@ __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, 
                 Pack<TIn, V> p[QU];
 #pragma unroll
                 for (int u = 0; u < QU; ++u)
-                    if (k0 + u < q) p[u] = *reinterpret_cast<const Pack<TIn, V> *>(s + (k0 + u) * src_step + e);
+                    if (k0 + u < q) {
+                        const Pack<TIn, V> *src = reinterpret_cast<const Pack<TIn, V> *>(s + (k0 + u) * src_step + e);
+                        p[u] = STREAM ? stream_load_pack(src) : *src;
+                    }
 #pragma unroll
                 for (int u = 0; u < QU; ++u)          // ascending index along the reduce direction
                     if (k0 + u < q) {
@@ -276,7 +374,8 @@ __global__ __launch_bounds__(256) void cube_reduce_kernel(CubeGeom g, int mode, 
             Pack<TOut, V> o;
 #pragma unroll
             for (int v = 0; v < V; ++v) store_f32<TOut>(&o.v[v], acc[v]);
-            *reinterpret_cast<Pack<TOut, V> *>(d + e) = o;
+            if (STREAM) stream_store_pack(reinterpret_cast<Pack<TOut, V> *>(d + e), o);
+            else *reinterpret_cast<Pack<TOut, V> *>(d + e) = o;
         }
     }
 }
@@ -288,10 +387,17 @@ int launch_reduce(const CubeGeom &g, int mode, int64_t rows, int64_t seg, const 
     dim3 grid((unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), 1, (unsigned)(g.q * g.q * g.q));
     const TIn *p = static_cast<const TIn *>(partials);
     TOut *s = static_cast<TOut *>(shards);
-    if (seg % 4 == 0)
-        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 4>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
+    // Partials larger than the 256 MB Infinity Cache are read once from HBM whatever the caches do:
+    // streaming accesses then keep them from displacing everything else (measured on 1 GB of fp32
+    // partials: 4.8 -> 5.1-5.4 TB/s); smaller ones may still be cache-resident from the producing kernel.
+    const int64_t n = (int64_t)g.q * g.q * g.q;
+    const bool streaming = n * g.q * rows * seg * (int64_t)sizeof(TIn) > (256ll << 20);
+    if (seg % 4 == 0 && streaming)
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 4, true>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
+    else if (seg % 4 == 0)
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 4, false>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
     else
-        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 1>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
+        hipLaunchKernelGGL((cube_reduce_kernel<TIn, TOut, 1, false>), grid, dim3(256), 0, stream, g, mode, rows, p, s, bias);
     return launch_status();
 }
 
@@ -314,12 +420,31 @@ int cube_move(const CubeGeom &g, int mode, int es, const void *src, void *dst, h
     case MV_PLACE_SCATTER: case MV_PLACE_ASSEMBLE: rows = g.pRs; seg = g.pCs; break;
     default: return CUBE3D_EINVAL;
     }
-    const int64_t nblk = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
-    if (nblk > 0x7fffffff || g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;
-    dim3 grid((unsigned)nblk, 1, (unsigned)(g.q * g.q * g.q));
     const char *s = static_cast<const char *>(src);
     char *d = static_cast<char *>(dst);
     const int64_t seg_bytes = seg * es;
+    if (g.q * g.q * g.q > 65535) return CUBE3D_ESHAPE;
+    if (mode == MV_GATHER_X || mode == MV_GATHER_DY || mode == MV_GATHER_W || mode == MV_PLACE_GATHER) {
+        // source-major: one shard per grid plane
+        const int64_t shard_rows = mode == MV_GATHER_W ? g.Kb : mode == MV_PLACE_GATHER ? g.pRs : g.Ms;
+        const int64_t shard_seg = mode == MV_GATHER_W ? g.Ns : mode == MV_PLACE_GATHER ? g.pCs : seg;
+        // every row start in source and destination is a multiple of the shard row length, so its
+        // alignment decides the widest safe vector
+        const int64_t row_bytes = shard_seg * es;
+        const int vec = row_bytes % 16 == 0 ? 16 : row_bytes % 4 == 0 ? 4 : row_bytes % 2 == 0 ? 2 : 1;
+        constexpr int U = 8;
+        const int64_t nb = (shard_rows * row_bytes / vec + 256 * U - 1) / (256 * U);
+        if (nb > 0x7fffffff) return CUBE3D_ESHAPE;
+        dim3 ggrid((unsigned)nb, 1, (unsigned)(g.q * g.q * g.q));
+        if (vec == 16) hipLaunchKernelGGL((cube_gather_kernel<i32x4, U>), ggrid, dim3(256), 0, stream, g, mode, es, s, d);
+        else if (vec == 4) hipLaunchKernelGGL((cube_gather_kernel<int, U>), ggrid, dim3(256), 0, stream, g, mode, es, s, d);
+        else if (vec == 2) hipLaunchKernelGGL((cube_gather_kernel<short, U>), ggrid, dim3(256), 0, stream, g, mode, es, s, d);
+        else hipLaunchKernelGGL((cube_gather_kernel<char, U>), ggrid, dim3(256), 0, stream, g, mode, es, s, d);
+        return launch_status();
+    }
+    const int64_t nblk = (rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
+    if (nblk > 0x7fffffff) return CUBE3D_ESHAPE;
+    dim3 grid((unsigned)nblk, 1, (unsigned)(g.q * g.q * g.q));
     // every segment start is a multiple of the segment length, so alignment of the
     // segment length decides the widest safe vector
     if (seg_bytes % 16 == 0)

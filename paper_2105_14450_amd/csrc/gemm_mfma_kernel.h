@@ -32,6 +32,7 @@
 // loads of a k-step are dealt out one per gap.
 #pragma once
 #include <atomic>
+#include <cstdlib>
 #include <mutex>
 #include <type_traits>
 
@@ -230,6 +231,9 @@ struct Params {
     // MAPPED instantiations only (then lda / ldb / ldc, the strides and the splits are unused)
     GemmMaps maps;
     KWalk ka, kb;
+#ifdef CUBE3D_PROFILE
+    unsigned long long *prof;   // 64 stamps per workgroup: (shader clock, 100 MHz clock) pairs
+#endif
 };
 
 // TOut: float or unsigned short (bf16 bits).  MAPPED: operands, output and the optional bias are
@@ -283,6 +287,20 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     const int lane = tid & 63, lane_id = lane;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
+#ifdef CUBE3D_PROFILE
+    int prof_n = 0;
+    auto stamp = [&]() {
+        if constexpr (MAPPED) return;
+        if (p.prof && tid == 0 && prof_n < 32) {
+            p.prof[(blockIdx.x * 32 + prof_n) * 2] = __builtin_readcyclecounter();
+            p.prof[(blockIdx.x * 32 + prof_n) * 2 + 1] = __builtin_amdgcn_s_memrealtime();
+        }
+        ++prof_n;
+    };
+#define CUBE3D_STAMP() stamp()
+#else
+#define CUBE3D_STAMP()
+#endif
 
     // ---- work items ------------------------------------------------------------------------------------
     // The workgroups are persistent: workgroup w takes the items w, w + gridDim.x, ...  An item is one
@@ -704,7 +722,9 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     k_tile(S0{}, T{}, T{}, STEADY{}, T{});
                     k_tile(S1{}, T{}, T{}, STEADY{}, F{});
                 }
+                CUBE3D_STAMP();   // two K-tiles in (stores may still be in flight)
                 k_tile(S2{}, T{}, T{}, STEADY{}, F{});
+                CUBE3D_STAMP();   // third K-tile done: its barrier waited for the previous item's stores
                 k_tile(S3{}, T{}, T{}, STEADY{}, F{});
                 for (int ps = 2; ps < passes; ++ps) {
                     k_tile(S0{}, T{}, T{}, STEADY{}, F{});
@@ -814,6 +834,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     };
 
     // ---- the items of this workgroup ----------------------------------------------------------------------
+    CUBE3D_STAMP();
     int item = blockIdx.x;
     decode_item(item);
     setup_sources();
@@ -822,6 +843,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     bool after_stores = false;
     while (true) {
         k_loop(after_stores, std::integral_constant<int, STORES>{});
+        CUBE3D_STAMP();   // K loop done
         after_stores = EPI_SEPARATE;   // only there are the stores younger than the next item's first loads
         const int64_t em0 = m0, en0 = n0;
         const int ebatch = batch, esplit = split;
@@ -834,9 +856,12 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 setup_sources();
                 early_loads();
             }
+            CUBE3D_STAMP();   // next item's first loads issued
             epilogue(em0, en0, ebatch, esplit);
+            CUBE3D_STAMP();   // epilogue issued
             if (!again) break;
             finish_prologue(std::integral_constant<int, STORES>{});
+            CUBE3D_STAMP();   // first fragments read
         } else {
             __syncthreads();   // all fragment reads of the stage buffers are done
             epilogue(em0, en0, ebatch, esplit);
@@ -920,6 +945,9 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
         p.kb = make_kwalk(g.maps->b_k, BKB / E::ELT);
     }
     p.y_items = g.batch * splits;
+#ifdef CUBE3D_PROFILE
+    p.prof = getenv("CUBE3D_PROF_PTR") ? reinterpret_cast<unsigned long long *>(strtoull(getenv("CUBE3D_PROF_PTR"), nullptr, 0)) : nullptr;
+#endif
     // persistent workgroups: as many as the chip holds at once, or one per item.  The item -> XCD
     // regrouping in the kernel needs a grid that is a multiple of 8 whenever a workgroup takes more
     // than one item.
