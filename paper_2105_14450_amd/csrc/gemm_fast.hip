@@ -64,7 +64,7 @@ Plan make_plan(const GemmArgs &g)
     if (g.Kc % (4 * ktile)) return p;           // the K loop takes the four LDS stages per pass
     const int64_t nk = g.Kc / ktile;
     const bool fits256 = g.Mo % 256 == 0 && g.No % 256 == 0;
-    const bool fits128 = (!fp8 || (g.a_kmajor && g.b_kmajor)) && g.Mo % 128 == 0 && g.No % 128 == 0;
+    const bool fits128 = g.Mo % 128 == 0 && g.No % 128 == 0;
     if (!fits256 && !fits128) return p;
     const int64_t tiles256 = fits256 ? (g.Mo / 256) * (g.No / 256) * g.batch : 0;
     if (fits256 && (tiles256 >= (3 * NUM_CU) / 4 || !fits128)) p.tile = 256;
@@ -74,7 +74,15 @@ Plan make_plan(const GemmArgs &g)
     // count from measured figures (microseconds: K-tile time per workgroup, fixed cost of a workgroup,
     // fixed cost and bandwidth of the reduction), smallest estimate wins.
     const int64_t tiles = (g.Mo / p.tile) * (g.No / p.tile) * g.batch;
-    const double t_ktile = p.tile == 128 ? 0.14 : 0.44, t_wg = 4.0, t_reduce = 3.0, bytes_per_us = 2.5e6;
+    // The figures are those of one MI355X under this kernel (shader clock 1.5-2.3 GHz depending on the
+    // data): a 64-byte K-tile takes a workgroup 1024 MFMA cycles at 256 x 256 and 256 at 128 x 128; start-up,
+    // first loads and epilogue of a workgroup 4 us; the reduction launch 3 us plus its traffic at
+    // 2.5 TB/s (short launches do not reach more).  They only rank split counts; a device twice as fast
+    // in everything picks the same plan.
+    constexpr double T_KTILE_256_US = 0.44, T_KTILE_128_US = 0.14, T_WORKGROUP_US = 4.0, T_REDUCE_LAUNCH_US = 3.0,
+                     REDUCE_BYTES_PER_US = 2.5e6;
+    const double t_ktile = p.tile == 128 ? T_KTILE_128_US : T_KTILE_256_US, t_wg = T_WORKGROUP_US, t_reduce = T_REDUCE_LAUNCH_US,
+                 bytes_per_us = REDUCE_BYTES_PER_US;
     const double out_bytes = (double)g.Mo * g.No * g.batch;
     int splits = 1;
     double best = 0;
@@ -138,13 +146,7 @@ int launch_for_layout(const GemmArgs &g, int splits, void *out, int64_t ld, int6
         if (g.a_kmajor && g.b_kmajor && (g.Kc * E::ELT / splits) % 512 == 0)
             return launch_cfg<E, T, T, 128, 4, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
     }
-    if constexpr (std::is_same<E, Fp8>::value && T == 128) {
-        // rows of 128 bytes are too short for the swizzle of an MN-major fp8 tile
-        if (!(g.a_kmajor && g.b_kmajor)) return CUBE3D_ENOTIMPL;
-        return launch_cfg<E, T, T, 64, 4, true, true, TOut>(g, splits, out, ld, bs, ss, g.alpha);
-    } else {
-        return launch_layout<E, T, T, 64, 4, TOut>(g, splits, out, ld, bs, ss, g.alpha);
-    }
+    return launch_layout<E, T, T, 64, 4, TOut>(g, splits, out, ld, bs, ss, g.alpha);
 }
 
 template <typename E, int T, typename TOut> int run_tile(const GemmArgs &g, const Plan &pl)

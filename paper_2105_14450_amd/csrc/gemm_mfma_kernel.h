@@ -96,7 +96,8 @@ struct Bf16 {
     static constexpr int KSTEP = 16;            // k per MFMA
     static constexpr int TR_ROWS = 4;           // k-rows covered by one transposing read
     static constexpr int FI = 4, PK = 1, PT = 2;
-    __device__ static __forceinline__ int mn_swz(int k) { return 4 * (k & 3); }
+    // slot permutation of an MN-major row (spr = 16-byte slots per row, at least 16): see MNMajorTile
+    __device__ static __forceinline__ int mn_swz(int k, int) { return 4 * (k & 3); }
     __device__ static __forceinline__ f32x16 mfma(FragI first, FragI second, f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second),
@@ -116,7 +117,9 @@ struct Fp8 {
     static constexpr int KSTEP = 64;
     static constexpr int TR_ROWS = 8;
     static constexpr int FI = 8, PK = 2, PT = 4;
-    __device__ static __forceinline__ int mn_swz(int k) { return 2 * (k & 7); }
+    // rows of 16 slots or more: the 8 k-rows of a transposing read go to 8 different slot pairs; rows of 8
+    // slots (128-byte rows): k-rows of equal parity lie 256 bytes apart, so the pair index is permuted by k / 2
+    __device__ static __forceinline__ int mn_swz(int k, int spr) { return spr >= 16 ? 2 * (k & 7) : 2 * ((k >> 1) & 3); }
     __device__ static __forceinline__ f32x16 mfma(FragI first, FragI second, f32x16 c)
     {
         // both operands e4m3 (format code 0), block scales 2^0
@@ -163,11 +166,12 @@ template <typename E, int COLS, int BKB> struct MNMajorTile {
     static constexpr int BYTES = KROWS * RB;
     static constexpr int CPW = BYTES / 1024 / WAVES;
     static_assert(BYTES % (1024 * WAVES) == 0, "tile must split into whole chunks per wavefront");
-    static_assert(SPR >= 16 && RB <= 1024, "the swizzle permutes slots inside aligned groups of 16");
+    static_assert((SPR >= 16 || (E::ELT == 1 && SPR == 8)) && RB <= 1024,
+                  "the swizzle permutes slots inside aligned groups of 16 (fp8 rows of 128 bytes: of 8)");
     __device__ static __forceinline__ int64_t lane_src(int wave, int lane, int64_t ld)
     {
         const int k = wave * RPC + lane / SPR;
-        const int slot = (lane % SPR) ^ E::mn_swz(k);
+        const int slot = (lane % SPR) ^ E::mn_swz(k, SPR);
         return (int64_t)k * ld + slot * (16 / E::ELT);
     }
     static constexpr int CHUNK_ROWS = WAVES * RPC;
@@ -184,7 +188,7 @@ template <typename E, int COLS, int BKB> struct MNMajorTile {
         const int g = lane / 16, s = lane % 16;
         const int k = (E::KSTEP / 2) * (g / 2) + s / LR;
         const int byte = (cb * 32 + 16 * (g % 2) + EPL * (s % LR)) * E::ELT;
-        return k * RB + (((byte / 16) ^ E::mn_swz(k)) * 16) + byte % 16;
+        return k * RB + (((byte / 16) ^ E::mn_swz(k, SPR)) * 16) + byte % 16;
     }
 };
 
@@ -379,7 +383,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     const int c = (lane % ATile::SPR) ^ KMajorTile<E, BM, BKB>::swz(first);
                     off = axis_offset(p.maps.a_mn, m0 + first + idx * ATile::CHUNK_ROWS) + c * EPS;
                 } else {
-                    const int slot = (lane % ATile::SPR) ^ E::mn_swz(first);
+                    const int slot = (lane % ATile::SPR) ^ E::mn_swz(first, ATile::SPR);
                     off = axis_offset(p.maps.a_mn, m0 + slot * EPS) + (int64_t)(first + idx * ATile::CHUNK_ROWS) * p.maps.a_k.u;
                 }
                 a_voff[idx] = (unsigned)(off * E::ELT);
@@ -394,7 +398,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     const int c = (lane % BTile::SPR) ^ KMajorTile<E, BN, BKB>::swz(first);
                     off = axis_offset(p.maps.b_mn, n0 + first + idx * BTile::CHUNK_ROWS) + c * EPS;
                 } else {
-                    const int slot = (lane % BTile::SPR) ^ E::mn_swz(first);
+                    const int slot = (lane % BTile::SPR) ^ E::mn_swz(first, BTile::SPR);
                     off = axis_offset(p.maps.b_mn, n0 + slot * EPS) + (int64_t)(first + idx * BTile::CHUNK_ROWS) * p.maps.b_k.u;
                 }
                 b_voff[idx] = (unsigned)(off * E::ELT);
