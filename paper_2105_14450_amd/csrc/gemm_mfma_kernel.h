@@ -232,6 +232,7 @@ struct Params {
     int y_items;                // batch * splits: an item is (y, output tile), item number = y * tiles + tile
     int64_t sSplit;             // output distance between the partial results of consecutive splits (elements)
     float alpha;
+    int stagger;                // start delay of the last workgroup in units of 10 ns (0: none); workgroup w waits w / grid of it
     // MAPPED instantiations only (then lda / ldb / ldc, the strides and the splits are unused)
     GemmMaps maps;
     KWalk ka, kb;
@@ -269,8 +270,15 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // reuse the stage memory.
     constexpr bool EPI_SEPARATE = BM * BN > 128 * 128;
     constexpr int JH = EPI_SEPARATE ? (TN * 32 * ESZ > 128 ? 128 / (32 * ESZ) : TN) : TN;
-    constexpr int EPI_STRIDE = JH * 32 * ESZ + 16;
-    constexpr int EPI_BYTES = 32 * EPI_STRIDE;
+    // A strip row is ROWB bytes, unpadded; its 16-byte slots are permuted by the row number so that both
+    // the lanes' writes (32 rows at one column) and the row-wise 16-byte reads spread over all banks.
+    // Two strips per wavefront where there is room: the next strip is converted and written while the
+    // reads of the previous one are in flight.
+    constexpr int ROWB = JH * 32 * ESZ;
+    constexpr int NBUF = MAPPED ? 1 : 2;
+    constexpr int STRIP_BYTES = 32 * ROWB;
+    constexpr int EPI_BYTES = NBUF * STRIP_BYTES;
+    static_assert(ROWB == 128 || ROWB == 256, "strip rows of 8 or 16 slots");
     constexpr int EPI_BASE = EPI_SEPARATE ? NSTAGE * STAGE_BYTES : 0;
     static_assert(TN % JH == 0, "whole strips");
     static_assert(KS >= 1 && BKB % (E::KSTEP * E::ELT) == 0, "K-tile must hold whole k-steps");
@@ -280,7 +288,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     static_assert(LPT % KS == 0, "the loads of a K-tile are dealt out evenly over its k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
     static_assert(NSTAGE * STAGE_BYTES <= 2 * 65536, "an LDS address is one of two lane registers plus a 16-bit immediate");
-    static_assert(EPI_BASE + WAVES * EPI_BYTES + BN * 4 <= (EPI_SEPARATE ? 160 * 1024 : NSTAGE * STAGE_BYTES),
+    static_assert(EPI_BASE + WAVES * EPI_BYTES + (MAPPED ? BN * 4 : 0) <= (EPI_SEPARATE ? 160 * 1024 : NSTAGE * STAGE_BYTES),
                   "epilogue staging (and the bias strip) must fit");
     static_assert((NSTAGE - 2) * LPT <= 63, "vmcnt range");
 
@@ -751,10 +759,13 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         }
     };
 
-    // ---- epilogue: 32 rows x JH column blocks at a time through a wave-private LDS strip --------------------
-    constexpr int LPR = JH * 32 * ESZ / 16;   // lanes per strip row
+    // ---- epilogue: 32 rows x JH column blocks at a time through wave-private LDS strips --------------------
+    constexpr int LPR = ROWB / 16;            // lanes per strip row = 16-byte slots per row
     constexpr int RPP = 64 / LPR;             // rows per pass
-    constexpr int STORES = TM * (TN / JH) * (32 / RPP);   // global stores per wavefront
+    constexpr int NPASS = 32 / RPP;           // passes (16-byte loads and global stores) per strip
+    constexpr int NSTRIP = TM * (TN / JH);    // strips per wavefront
+    constexpr int STORES = NSTRIP * NPASS;    // global stores per wavefront
+    constexpr int RP256 = 256 / ROWB;         // strip rows per 256 bytes of LDS (all banks once)
     auto epilogue_impl = [&](auto scaled_c, int64_t em0, int64_t en0, int ebatch, int esplit) {
         constexpr bool scaled = decltype(scaled_c)::value;   // alpha != 1: one more multiply per element
         // The lane number and the row stride are made opaque here, so that the strip and row addresses
@@ -779,54 +790,96 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         const float alpha = p.alpha;
         int64_t row_stride = MAPPED ? p.maps.c_m.u : p.ldc;
         asm volatile("" : "+s"(row_stride));
+        // write side: this lane's row of the strip, the byte inside a slot, and its rows' slot permutation
+        const int wr_row = lane & 31;
+        const unsigned wr_base = (unsigned)(wr_row * ROWB + (ESZ == 2 ? 8 * (lane >> 5) : 0));
+        const unsigned wr_perm = (unsigned)(((wr_row / RP256) & (LPR - 1)) << 4);
+        // read side: row (lane / LPR) of a pass, slot (lane % LPR); the permutation of pass `ps` differs from
+        // that of pass 0 by a constant (RPP is a multiple of RP256)
+        const int rd_row = lane / LPR;
+        const unsigned rd_base = (unsigned)(rd_row * ROWB);
+        const unsigned rd_slot = (unsigned)(((lane % LPR) ^ ((rd_row / RP256) & (LPR - 1))) << 4);
+
+        auto write_strip = [&](int sidx, char *buf) {
+            const int i = sidx / (TN / JH), jh = sidx % (TN / JH);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            int64_t strip_m = 0;   // MAPPED: where this 32-row strip (inside one shard) starts
-            if constexpr (MAPPED) strip_m = axis_offset(p.maps.c_m, em0 + wm * WM + i * 32);
+            for (int jj = 0; jj < JH; ++jj) {
+                const int j = jh * JH + jj;
 #pragma unroll
-            for (int jh = 0; jh < TN / JH; ++jh) {
-#pragma unroll
-                for (int jj = 0; jj < JH; ++jj) {
-                    const int j = jh * JH + jj;
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        // registers 4g..4g+3 of lane: row lane%32, columns j*32 + 8g + 4*(lane/32) + 0..3
-                        char *dst = epi + (lane & 31) * EPI_STRIDE + (jj * 32 + 8 * g + 4 * (lane >> 5)) * ESZ;
-                        float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1];
-                        float v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
-                        if (scaled) { v0 *= alpha; v1 *= alpha; v2 *= alpha; v3 *= alpha; }
-                        if constexpr (MAPPED) {
-                            const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
-                            v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
-                        }
-                        if (ESZ == 4) {
-                            f32x4 v = {v0, v1, v2, v3};
-                            *reinterpret_cast<f32x4 *>(dst) = v;
-                        } else {
-                            uint2 v;
-                            v.x = pack_bf16x2(v0, v1);
-                            v.y = pack_bf16x2(v2, v3);
-                            *reinterpret_cast<uint2 *>(dst) = v;
-                        }
+                for (int g = 0; g < 4; ++g) {
+                    // registers 4g..4g+3 of lane: row lane%32, columns j*32 + 8g + 4*(lane/32) + 0..3
+                    const unsigned cb = (unsigned)((jj * 32 + 8 * g) * ESZ);     // byte of column 8g in the strip row
+                    const unsigned slot16 = ESZ == 2 ? (cb & ~15u) : cb;          // fp32: the lane half picks the next slot
+                    unsigned ad = wr_base + ((slot16 + (ESZ == 4 ? 16u * (unsigned)(lane >> 5) : 0u)) ^ wr_perm);
+                    char *dst = buf + ad;
+                    float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1];
+                    float v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
+                    if (scaled) { v0 *= alpha; v1 *= alpha; v2 *= alpha; v3 *= alpha; }
+                    if constexpr (MAPPED) {
+                        const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
+                        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+                    }
+                    if (ESZ == 4) {
+                        f32x4 v = {v0, v1, v2, v3};
+                        *reinterpret_cast<f32x4 *>(dst) = v;
+                    } else {
+                        uint2 v;
+                        v.x = pack_bf16x2(v0, v1);
+                        v.y = pack_bf16x2(v2, v3);
+                        *reinterpret_cast<uint2 *>(dst) = v;
                     }
                 }
-                int64_t col = 0;   // MAPPED: where this lane's 16 bytes of the strip row go
-                if constexpr (MAPPED) col = axis_offset(p.maps.c_n, en0 + wn * WN + jh * JH * 32 + (lane % LPR) * (16 / ESZ));
+            }
+        };
+        auto read_strip = [&](const char *buf, i32x4 (&v)[NPASS]) {
 #pragma unroll
-                for (int pass = 0; pass < 32 / RPP; ++pass) {
-                    const int row = pass * RPP + lane / LPR;
-                    const i32x4 v = *reinterpret_cast<const i32x4 *>(epi + row * EPI_STRIDE + (lane % LPR) * 16);
-                    char *gp;
-                    if constexpr (!MAPPED)
-                        gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * row_stride + jh * JH * 32) + (lane % LPR) * 16;
-                    else gp = reinterpret_cast<char *>(C + col + strip_m + (int64_t)row * row_stride);
-                    // streaming store: the product is not read again by this kernel, and kept out of the
-                    // caches it leaves them to the operand panels that other XCDs still fetch (measured
-                    // on the large bf16 shapes, three products back to back: +1.4 %, dX +3.8 %)
-                    __builtin_nontemporal_store(v, reinterpret_cast<i32x4 *>(gp));
-                }
+            for (int ps = 0; ps < NPASS; ++ps) {
+                const unsigned perm_ps = (unsigned)((((ps * RPP) / RP256) & (LPR - 1)) << 4);
+                v[ps] = *reinterpret_cast<const i32x4 *>(buf + rd_base + ps * RPP * ROWB + (rd_slot ^ perm_ps));
+            }
+        };
+        auto store_strip = [&](int sidx, const i32x4 (&v)[NPASS]) {
+            const int i = sidx / (TN / JH), jh = sidx % (TN / JH);
+            int64_t strip_m = 0, col = 0;   // MAPPED: where this 32-row strip (inside one shard) starts, and this lane's 16 bytes
+            if constexpr (MAPPED) {
+                strip_m = axis_offset(p.maps.c_m, em0 + wm * WM + i * 32);
+                col = axis_offset(p.maps.c_n, en0 + wn * WN + jh * JH * 32 + (lane % LPR) * (16 / ESZ));
+            }
+#pragma unroll
+            for (int ps = 0; ps < NPASS; ++ps) {
+                const int row = ps * RPP + rd_row;
+                char *gp;
+                if constexpr (!MAPPED)
+                    gp = reinterpret_cast<char *>(C + (int64_t)(i * 32 + row) * row_stride + jh * JH * 32) + (lane % LPR) * 16;
+                else gp = reinterpret_cast<char *>(C + col + strip_m + (int64_t)row * row_stride);
+                // streaming store: the product is not read again by this kernel, and kept out of the
+                // caches it leaves them to the operand panels that other XCDs still fetch (measured
+                // on the large bf16 shapes, three products back to back: +1.4 %, dX +3.8 %)
+                __builtin_nontemporal_store(v[ps], reinterpret_cast<i32x4 *>(gp));
+            }
+        };
+
+        if constexpr (NBUF == 2) {
+            // strip s is written while the reads of strip s-1 are in flight; its stores follow those reads
+            i32x4 held[2][NPASS];
+#pragma unroll
+            for (int sidx = 0; sidx < NSTRIP; ++sidx) {
+                write_strip(sidx, epi + (sidx & 1) * STRIP_BYTES);
+                __builtin_amdgcn_sched_barrier(0);
+                if (sidx > 0) store_strip(sidx - 1, held[(sidx - 1) & 1]);
+                read_strip(epi + (sidx & 1) * STRIP_BYTES, held[sidx & 1]);
                 // one strip at a time: without this the scheduler pulls all accumulator reads to the
                 // front and needs a register for every output element at once
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            store_strip(NSTRIP - 1, held[(NSTRIP - 1) & 1]);
+        } else {
+#pragma unroll
+            for (int sidx = 0; sidx < NSTRIP; ++sidx) {
+                i32x4 held[NPASS];
+                write_strip(sidx, epi);
+                read_strip(epi, held);
+                store_strip(sidx, held);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -843,6 +896,16 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     decode_item(item);
     setup_sources();
     early_loads();
+    if (p.stagger > 0) {
+        // Staggered start (launches in which a workgroup takes several items): the workgroups reach
+        // their epilogues at different times, so that the output of one round of items is not written
+        // by all CUs at once (the fabric takes 4.5 TB/s of writes; a burst of 128 KB per CU from every CU
+        // holds each of them up for microseconds, four times per launch).  The first loads are in flight
+        // meanwhile.  The wait ends on a free-running clock, whatever else happens.
+        const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+        const unsigned long long wait = (unsigned long long)p.stagger * blockIdx.x / gridDim.x;
+        while (__builtin_amdgcn_s_memrealtime() - t0 < wait) __builtin_amdgcn_s_sleep(16);
+    }
     finish_prologue(std::integral_constant<int, 0>{});
     bool after_stores = false;
     while (true) {
@@ -943,6 +1006,7 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
     p.splits = splits;
     p.sSplit = out_split_stride;
     p.alpha = alpha;
+    p.stagger = 0;
     if (MAPPED) {
         p.maps = *g.maps;
         p.ka = make_kwalk(g.maps->a_k, BKB / E::ELT);
@@ -960,6 +1024,12 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
     const int64_t resident = (int64_t)num_compute_units() * per_cu / 8 * 8;
     if (items >= (1ll << 31) || resident < 8) return CUBE3D_ENOTIMPL;
     dim3 grid((unsigned)(items < resident ? items : resident), 1, 1);
+    // Several items per workgroup: spread the workgroups' starts over about the time the fabric needs
+    // to take one round's output (all resident tiles, at 4.5 TB/s of writes; 10 ns units), see the kernel.
+    if (items > resident) p.stagger = (int)((int64_t)grid.x * BM * BN * (int64_t)sizeof(TOut) / 56000);
+#ifdef CUBE3D_STAGGER_ENV
+    if (items > resident && getenv("CUBE3D_STAGGER")) p.stagger = atoi(getenv("CUBE3D_STAGGER"));
+#endif
     hipLaunchKernelGGL(kern, grid, dim3(256), LDS, g.stream, p);
     return launch_status();
 }
