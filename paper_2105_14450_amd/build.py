@@ -8,8 +8,10 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
-LIB = os.path.join(HERE, "libcube3d.so")
-OBJDIR = os.path.join(HERE, "_build")
+# CUBE3D_OUT: another file name for the library (a variant build, e.g. with CUBE3D_EXTRA_FLAGS=-DCUBE3D_PROFILE,
+# beside the product's libcube3d.so); its objects go to a folder of their own
+LIB = os.path.join(HERE, os.environ.get("CUBE3D_OUT", "libcube3d.so"))
+OBJDIR = os.path.join(HERE, "_build" if "CUBE3D_OUT" not in os.environ else "_build_" + os.environ["CUBE3D_OUT"].replace(".", "_"))
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
@@ -80,7 +82,10 @@ def _compile(src):
         glob.glob(os.path.join(OBJDIR, os.path.splitext(base)[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s"))
     for path in asm:
         spilled += _spills_in_k_loops(path)
-    if spilled:
+    # (a profiling build carries the time stamps' registers as well: its spills are reported, not refused)
+    if spilled and "-DCUBE3D_PROFILE" in FLAGS:
+        sys.stderr.write("note: register spills in %s: %d kernels\n" % (base, len(set(spilled))))
+    elif spilled:
         raise RuntimeError("register spills in %s: %s" % (base, sorted(set(spilled))))
     return obj
 
