@@ -40,13 +40,40 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 struct AxisMap {
     int32_t P1, P2;
     int64_t s1, s2, u;
+    // Filled by prepare_axis_map(): constants for dividing an index below 2^31 by P1 / P2 exactly
+    // without a divide instruction,  x / P = (x * M) >> N  with N = 31 + ceil(log2 P) and
+    // M = ceil(2^N / P) (at most 34 bits, so x * M stays below 2^64).
+    uint64_t M1, M2;
+    int32_t N1, N2;
 };
+
+inline void prepare_axis_map(AxisMap &m)
+{
+    auto magic = [](int32_t P, uint64_t *M, int32_t *N) {
+        int L = 0;
+        while ((1ll << L) < P) ++L;
+        *N = 31 + L;
+        *M = (uint64_t)(((((unsigned __int128)1) << *N) + (unsigned)P - 1) / (unsigned)P);
+    };
+    magic(m.P1, &m.M1, &m.N1);
+    magic(m.P2, &m.M2, &m.N2);
+}
 
 __host__ __device__ __forceinline__ int64_t axis_offset(const AxisMap &m, int64_t x)
 {
     const uint32_t xx = (uint32_t)x;
     const uint32_t hi = xx / (uint32_t)m.P1, r1 = xx - hi * (uint32_t)m.P1;
     const uint32_t mid = r1 / (uint32_t)m.P2, lo = r1 - mid * (uint32_t)m.P2;
+    return (int64_t)hi * m.s1 + (int64_t)mid * m.s2 + (int64_t)lo * m.u;
+}
+
+// The same value for a prepared map and 0 <= x < 2^31, with multiplications in place of the divisions
+// (a division by a run-time divisor is some forty instructions on the vector ALU).
+__device__ __forceinline__ int64_t axis_offset_fast(const AxisMap &m, int64_t x)
+{
+    const uint32_t xx = (uint32_t)x;
+    const uint32_t hi = (uint32_t)(((uint64_t)xx * m.M1) >> m.N1), r1 = xx - hi * (uint32_t)m.P1;
+    const uint32_t mid = (uint32_t)(((uint64_t)r1 * m.M2) >> m.N2), lo = r1 - mid * (uint32_t)m.P2;
     return (int64_t)hi * m.s1 + (int64_t)mid * m.s2 + (int64_t)lo * m.u;
 }
 

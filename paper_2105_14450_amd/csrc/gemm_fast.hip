@@ -14,7 +14,8 @@ struct Plan {
 };
 
 // What the map-addressed instantiations assume of an index placement.
-//   walked (the contraction index): a K-tile of `kpt` indices never straddles a shard
+//   walked (the contraction index): shards are whole passes over the LDS stages long (`granule` indices),
+//     so that a K-tile never straddles a shard and boundaries fall on pass boundaries
 //   contiguous: the index that is contiguous in memory moves in 16-byte pieces of `piece` elements
 //   rows: a run of `run` consecutive indices (a load chunk, an output strip) lies in one shard
 bool map_ok(const AxisMap &m, int64_t extent, int64_t stride_align, bool contiguous, int64_t granule)
@@ -39,13 +40,15 @@ Plan make_plan(const GemmArgs &g)
         if (g.batch != 1 || g.Mo >= (1ll << 31) || g.No >= (1ll << 31) || g.Kc >= (1ll << 31)) return p;
         if (g.out_dtype != CUBE3D_F32 && g.out_dtype != CUBE3D_BF16) return p;
         const GemmMaps &m = *g.maps;
-        const int64_t kpt = 64 / es;            // contraction indices per 64-byte K-tile
+        // contraction indices per pass over the LDS stages (four 64-byte K-tiles, or two of 128 bytes): shards
+        // and blocks of a walked index must be whole passes long
+        const int64_t kpt = 256 / es;
         const int64_t oalign = g.out_dtype == CUBE3D_F32 ? 4 : 8;
         if (!map_ok(m.a_k, g.Kc, align, g.a_kmajor, kpt) || !map_ok(m.b_k, g.Kc, align, g.b_kmajor, kpt)) return p;
         if (!map_ok(m.a_mn, g.Mo, align, !g.a_kmajor, 16) || !map_ok(m.b_mn, g.No, align, !g.b_kmajor, 16)) return p;
         if (!map_ok(m.c_m, g.Mo, oalign, false, 32) || !map_ok(m.c_n, g.No, oalign, true, oalign)) return p;
         if (m.bias && !map_ok(m.bias_n, g.No, 1, true, 4)) return p;
-        if (g.Kc % (4 * kpt)) return p;          // the K loop takes the four LDS stages per pass
+        if (g.Kc % kpt) return p;                // the K loop takes the four LDS stages per pass
         // the kernel addresses an operand as buffer start + 32-bit byte offset
         if ((axis_offset(m.a_mn, g.Mo - 1) + axis_offset(m.a_k, g.Kc - 1) + 1) * es >= (1ll << 32)) return p;
         if ((axis_offset(m.b_mn, g.No - 1) + axis_offset(m.b_k, g.Kc - 1) + 1) * es >= (1ll << 32)) return p;

@@ -16,8 +16,8 @@ template <typename E, int T, typename TOut> int launch_mapped(const GemmArgs &g)
     if (g.a_kmajor && !g.b_kmajor)
         return launch_cfg<E, T, T, 64, 4, true, false, TOut, true>(g, 1, g.C, 0, 0, 0, g.alpha);
     if (g.a_kmajor && g.b_kmajor) {
-        // 128-byte K-tiles (whole cache lines per row) when no such tile straddles a shard
-        if (T == 256 && g.Kc * E::ELT % 256 == 0 && g.maps->a_k.P2 * E::ELT % 128 == 0 && g.maps->b_k.P2 * E::ELT % 128 == 0)
+        // 128-byte K-tiles (whole cache lines per row), two stages: a pass is 256 bytes as with four 64-byte tiles
+        if (T == 256 && g.Kc * E::ELT % 256 == 0 && g.maps->a_k.P2 * E::ELT % 256 == 0 && g.maps->b_k.P2 * E::ELT % 256 == 0)
             return launch_cfg<E, T, T, 128, 2, true, true, TOut, true>(g, 1, g.C, 0, 0, 0, g.alpha);
         return launch_cfg<E, T, T, 64, 4, true, true, TOut, true>(g, 1, g.C, 0, 0, 0, g.alpha);
     }

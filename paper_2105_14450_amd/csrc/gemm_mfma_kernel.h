@@ -302,16 +302,19 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
 #ifdef CUBE3D_PROFILE
     int prof_n = 0;
     auto stamp = [&]() {
-        if constexpr (MAPPED) return;
-        if (p.prof && tid == 0 && prof_n < 32) {
+        // (wave-uniform condition: all lanes of the first wavefront store the same two values)
+        if (p.prof && wave == 0 && prof_n < 32) {
             p.prof[(blockIdx.x * 32 + prof_n) * 2] = __builtin_readcyclecounter();
             p.prof[(blockIdx.x * 32 + prof_n) * 2 + 1] = __builtin_amdgcn_s_memrealtime();
         }
         ++prof_n;
     };
 #define CUBE3D_STAMP() stamp()
+// inside the K loop only for plain operands: the map-addressed K loop has no scalar registers to spare
+#define CUBE3D_STAMP_LOOP() do { if constexpr (!MAPPED) stamp(); } while (0)
 #else
 #define CUBE3D_STAMP()
+#define CUBE3D_STAMP_LOOP()
 #endif
 
     // ---- work items ------------------------------------------------------------------------------------
@@ -381,6 +384,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         constexpr int EPS = 16 / E::ELT;   // elements per 16-byte slot
         a_base = static_cast<const char *>(p.A);
         b_base = static_cast<const char *>(p.B);
+        a_step = p.ka.step * E::ELT;
+        b_step = p.kb.step * E::ELT;
         wa.c1 = wa.c2 = wb.c1 = wb.c2 = 0;
         {
             const int first = wave * ATile::RPC + lane / ATile::SPR;   // tile row (K-major) or k-row (MN-major)
@@ -389,10 +394,10 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 int64_t off;
                 if constexpr (AK) {
                     const int c = (lane % ATile::SPR) ^ KMajorTile<E, BM, BKB>::swz(first);
-                    off = axis_offset(p.maps.a_mn, m0 + first + idx * ATile::CHUNK_ROWS) + c * EPS;
+                    off = axis_offset_fast(p.maps.a_mn, m0 + first + idx * ATile::CHUNK_ROWS) + c * EPS;
                 } else {
                     const int slot = (lane % ATile::SPR) ^ E::mn_swz(first, ATile::SPR);
-                    off = axis_offset(p.maps.a_mn, m0 + slot * EPS) + (int64_t)(first + idx * ATile::CHUNK_ROWS) * p.maps.a_k.u;
+                    off = axis_offset_fast(p.maps.a_mn, m0 + slot * EPS) + (int64_t)(first + idx * ATile::CHUNK_ROWS) * p.maps.a_k.u;
                 }
                 a_voff[idx] = (unsigned)(off * E::ELT);
             }
@@ -404,10 +409,10 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 int64_t off;
                 if constexpr (BKM) {
                     const int c = (lane % BTile::SPR) ^ KMajorTile<E, BN, BKB>::swz(first);
-                    off = axis_offset(p.maps.b_mn, n0 + first + idx * BTile::CHUNK_ROWS) + c * EPS;
+                    off = axis_offset_fast(p.maps.b_mn, n0 + first + idx * BTile::CHUNK_ROWS) + c * EPS;
                 } else {
                     const int slot = (lane % BTile::SPR) ^ E::mn_swz(first, BTile::SPR);
-                    off = axis_offset(p.maps.b_mn, n0 + slot * EPS) + (int64_t)(first + idx * BTile::CHUNK_ROWS) * p.maps.b_k.u;
+                    off = axis_offset_fast(p.maps.b_mn, n0 + slot * EPS) + (int64_t)(first + idx * BTile::CHUNK_ROWS) * p.maps.b_k.u;
                 }
                 b_voff[idx] = (unsigned)(off * E::ELT);
             }
@@ -424,17 +429,22 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                           wave_lds + stage * STAGE_BYTES + A_BYTES + (idx - ATile::CPW) * (WAVES * 1024));
     };
     // Move an operand's scalar pointer to the next K-tile.  MAPPED: the walk along the contraction
-    // index steps through shards and blocks; the corrections are selected with masks, because a
-    // branch in the K loop holds up the MFMA stream far longer than a dozen scalar instructions.
-    // Even so the scalar work of one step is more than fits behind one MFMA, so inside the K loop it
-    // is dealt out in three parts over three gaps (walk_part), and only the final add sits behind
-    // the operand's last load (walk_apply).
+    // index steps through shards and blocks.  Shards and blocks are whole passes over the LDS stages
+    // long (the launcher checks it), so a pointer can only cross a boundary when it moves onto a
+    // K-tile whose number is a multiple of NSTAGE: those moves ("checked") look at the position and
+    // add the jump to the next shard or block, all others add the plain step like an ordinary
+    // operand.  The corrections of a checked move are selected with masks, because a branch in the K
+    // loop holds up the MFMA stream far longer than a dozen scalar instructions; even so its scalar
+    // work is more than fits behind one MFMA, so inside the K loop it is dealt out in three parts
+    // over three gaps (walk_part), and only the final add sits behind the operand's last load
+    // (walk_apply).  The position counts the contraction indices since the last boundary, one pass
+    // at a time.
     auto walk_part = [&](Walk &w, const KWalk &k, int part) {
         if constexpr (MAPPED) {
-            constexpr int KPT = BKB / E::ELT;   // contraction indices per K-tile
+            constexpr int PASS = NSTAGE * (BKB / E::ELT);   // contraction indices per pass over the stages
             if (part == 0) {
-                w.c1 += KPT;
-                w.c2 += KPT;
+                w.c1 += PASS;
+                w.c2 += PASS;
                 w.m1 = eq_mask(w.c1, k.P1);
                 w.m2 = eq_mask(w.c2, k.P2) & ~w.m1;
             } else if (part == 1) {
@@ -445,18 +455,18 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             }
         }
     };
-    auto walk_apply = [&](const char *&base, int64_t plain_step, const Walk &w) {
-        if constexpr (!MAPPED) base += plain_step;
-        else base += w.delta;
+    auto walk_apply = [&](const char *&base, int64_t plain_step, const Walk &w, bool checked) {
+        if (MAPPED && checked) base += w.delta;
+        else base += plain_step;
     };
-    // the whole step at once (prologue)
-    auto advance_a = [&]() {
-        walk_part(wa, p.ka, 0); walk_part(wa, p.ka, 1); walk_part(wa, p.ka, 2);
-        walk_apply(a_base, a_step, wa);
+    // whole moves at once (prologue): plain, or checked
+    auto advance_a = [&](bool checked = false) {
+        if (checked) { walk_part(wa, p.ka, 0); walk_part(wa, p.ka, 1); walk_part(wa, p.ka, 2); }
+        walk_apply(a_base, a_step, wa, checked);
     };
-    auto advance_b = [&]() {
-        walk_part(wb, p.kb, 0); walk_part(wb, p.kb, 1); walk_part(wb, p.kb, 2);
-        walk_apply(b_base, b_step, wb);
+    auto advance_b = [&](bool checked = false) {
+        if (checked) { walk_part(wb, p.kb, 0); walk_part(wb, p.kb, 1); walk_part(wb, p.kb, 2); }
+        walk_apply(b_base, b_step, wb, checked);
     };
 
     // ---- lane-constant LDS addresses of the fragment reads; every read adds an immediate -------------
@@ -574,7 +584,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             __builtin_amdgcn_s_barrier();   // everyone has left the last K-tile of the previous item
 #pragma unroll
             for (int idx = 0; idx < ATile::CPW; ++idx) issue_load(idx, 1);
-            advance_a();
+            advance_a(true);   // onto K-tile 2: a multiple of the two stages
             tile_barrier<(ATile::CPW + stores <= 63 ? ATile::CPW + stores : 63)>();
         } else {
             tile_barrier<((PRE - 1) * LPT + stores <= 63 ? (PRE - 1) * LPT + stores : 63)>();
@@ -604,6 +614,13 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         constexpr int pre = (stage + NSTAGE - 1) % NSTAGE;      // stage the loads of this tile body go to
         constexpr int next = (stage + 1) % NSTAGE;
         constexpr int parity = (stage * KS) & 1;                // fragment buffer holding this tile's k-step 0
+        // MAPPED: the moves of this tile body that land on a K-tile number that is a multiple of NSTAGE.
+        // Four stages: tile body kt loads tile kt+3 and moves both pointers onto kt+4: checked where
+        // kt is a multiple of 4.  Two stages: body kt moves B (the first to move) onto kt+2, checked
+        // for even kt, and A onto kt+3, checked for odd kt.
+        constexpr bool chk_first = stage == 0;
+        constexpr bool chk_second = NSTAGE == 2 ? stage == 1 : stage == 0;
+        constexpr bool chk_a = NSTAGE == 2 ? chk_second : chk_first, chk_b = NSTAGE == 2 ? chk_first : chk_second;
         // the LDS targets of this tile body's loads are formed here, one scalar add each, not kept
         // in registers across the whole loop
         asm volatile("" : "+s"(wave_lds));
@@ -632,14 +649,14 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (MAPPED) {
-                    // scalar work of the K walk: the operand whose pointer moves first in this tile body
-                    // (A with four stages, B with two) in the first twelfth-steps, the other from the middle
+                    // scalar work of the checked moves of this tile body: the operand whose pointer moves
+                    // first (A with four stages, B with two) in the first twelfth-steps, the other from the middle
                     const int f = ks * NM + g;
                     constexpr int TOTG = KS * NM;
 #pragma unroll
                     for (int part = 0; part < 3; ++part) {
-                        const bool first_moves = NSTAGE == 2 ? has_next : more;    // its loads are issued at all
-                        const bool second_moves = more;
+                        const bool first_moves = (NSTAGE == 2 ? has_next : more) && chk_first;    // its loads are issued at all
+                        const bool second_moves = more && chk_second;
                         if (f == (part * TOTG) / 12 && first_moves) {
                             if (NSTAGE == 2) walk_part(wb, p.kb, part);
                             else walk_part(wa, p.ka, part);
@@ -665,8 +682,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                         if (((2 * l + 1) * NM) / (2 * LPK) != g) continue;
                         issue_load(ks * LPK + l, pre);
                         // behind an operand's last load of the tile: its pointer moves on
-                        if (ks * LPK + l == ATile::CPW - 1) walk_apply(a_base, a_step, wa);
-                        if (ks * LPK + l == LPT - 1) walk_apply(b_base, b_step, wb);
+                        if (ks * LPK + l == ATile::CPW - 1) walk_apply(a_base, a_step, wa, chk_a);
+                        if (ks * LPK + l == LPT - 1) walk_apply(b_base, b_step, wb, chk_b);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -675,7 +692,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     for (int l = 0; l < BTile::CPW; ++l) {
                         if (((2 * l + 1) * NM) / (2 * BTile::CPW) != g) continue;
                         issue_load(ATile::CPW + l, next);
-                        if (l == BTile::CPW - 1) walk_apply(b_base, b_step, wb);
+                        if (l == BTile::CPW - 1) walk_apply(b_base, b_step, wb, chk_b);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -684,7 +701,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     for (int l = 0; l < ATile::CPW; ++l) {
                         if (((2 * l + 1) * NM) / (2 * ATile::CPW) != g) continue;
                         issue_load(l, stage);
-                        if (l == ATile::CPW - 1) walk_apply(a_base, a_step, wa);
+                        if (l == ATile::CPW - 1) walk_apply(a_base, a_step, wa, chk_a);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -734,9 +751,9 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     k_tile(S0{}, T{}, T{}, STEADY{}, T{});
                     k_tile(S1{}, T{}, T{}, STEADY{}, F{});
                 }
-                CUBE3D_STAMP();   // two K-tiles in (stores may still be in flight)
+                CUBE3D_STAMP_LOOP();   // two K-tiles in (stores may still be in flight)
                 k_tile(S2{}, T{}, T{}, STEADY{}, F{});
-                CUBE3D_STAMP();   // third K-tile done: its barrier waited for the previous item's stores
+                CUBE3D_STAMP_LOOP();   // third K-tile done: its barrier waited for the previous item's stores
                 k_tile(S3{}, T{}, T{}, STEADY{}, F{});
                 for (int ps = 2; ps < passes; ++ps) {
                     k_tile(S0{}, T{}, T{}, STEADY{}, F{});
@@ -783,7 +800,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             // one add per output element whether or not there is a bias: no branch inside the unrolled loops
             float *strip = reinterpret_cast<float *>(smem + EPI_BASE + WAVES * EPI_BYTES);
             __syncthreads();   // the previous item's strip has been read
-            for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias ? p.maps.bias[axis_offset(p.maps.bias_n, en0 + x)] : 0.f;
+            for (int x = tid; x < BN; x += 256) strip[x] = p.maps.bias ? p.maps.bias[axis_offset_fast(p.maps.bias_n, en0 + x)] : 0.f;
             __syncthreads();
             bias_lds = strip + wn * WN + 4 * (lane >> 5);
         }
@@ -842,8 +859,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
             const int i = sidx / (TN / JH), jh = sidx % (TN / JH);
             int64_t strip_m = 0, col = 0;   // MAPPED: where this 32-row strip (inside one shard) starts, and this lane's 16 bytes
             if constexpr (MAPPED) {
-                strip_m = axis_offset(p.maps.c_m, em0 + wm * WM + i * 32);
-                col = axis_offset(p.maps.c_n, en0 + wn * WN + jh * JH * 32 + (lane % LPR) * (16 / ESZ));
+                strip_m = axis_offset_fast(p.maps.c_m, em0 + wm * WM + i * 32);
+                col = axis_offset_fast(p.maps.c_n, en0 + wn * WN + jh * JH * 32 + (lane % LPR) * (16 / ESZ));
             }
 #pragma unroll
             for (int ps = 0; ps < NPASS; ++ps) {
@@ -1009,6 +1026,8 @@ int launch_cfg(const GemmArgs &g, int splits, void *out, int64_t out_ld, int64_t
     p.stagger = 0;
     if (MAPPED) {
         p.maps = *g.maps;
+        for (AxisMap *m : {&p.maps.a_mn, &p.maps.a_k, &p.maps.b_mn, &p.maps.b_k, &p.maps.c_m, &p.maps.c_n, &p.maps.bias_n})
+            prepare_axis_map(*m);
         p.ka = make_kwalk(g.maps->a_k, BKB / E::ELT);
         p.kb = make_kwalk(g.maps->b_k, BKB / E::ELT);
     }
