@@ -592,17 +592,22 @@ __global__ __launch_bounds__(64 * FIN_WAVES) void cube_bias_bwd_finish_kernel(Cu
     const int a = j;
     const int total = g.q * g.q * NRG, per = (total + FIN_WAVES - 1) / FIN_WAVES;
     const int t_lo = wave * per < total ? wave * per : total, t_hi = t_lo + per < total ? t_lo + per : total;
+    // term t = (source processor (i', a, b'), its row group): walked with counters, one division per wavefront
+    int src = t_lo / NRG, rg = t_lo - src * NRG;
+    int si = src / g.q, sb = src - si * g.q;
+    const float *col = part + (int64_t)i * g.Ns + c;
     float acc = 0.f;
     for (int t0 = t_lo; t0 < t_hi; t0 += U) {
         float v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int t = t0 + u;
             v[u] = 0.f;
-            if (live && t < t_hi) {
-                const int src = t / NRG, rg = t - src * NRG;
-                const int64_t rr = rank_index(g, src / g.q, a, src % g.q);
-                v[u] = part[(rr * NRG + rg) * g.Nb + (int64_t)i * g.Ns + c];
+            if (t0 + u < t_hi) {
+                if (live) v[u] = col[(rank_index(g, si, a, sb) * NRG + rg) * g.Nb];
+                if (++rg == NRG) {
+                    rg = 0;
+                    if (++sb == g.q) { sb = 0; ++si; }
+                }
             }
         }
 #pragma unroll
