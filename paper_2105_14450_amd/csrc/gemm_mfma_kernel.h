@@ -192,15 +192,6 @@ template <typename E, int COLS, int BKB> struct MNMajorTile {
     }
 };
 
-// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
-__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi)
-{
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
-}
-
 // Advance of a map-addressed operand from one K-tile to the next (all values in elements): the
 // plain step inside a shard, and the corrections when the tile walks off a shard (jump2) or off
 // a block (jump1) of the contraction index.
