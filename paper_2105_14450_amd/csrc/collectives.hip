@@ -579,7 +579,7 @@ __global__ __launch_bounds__(64 * FIN_WAVES) void cube_bias_bwd_finish_kernel(Cu
                                                                               float *__restrict__ db)
 {
     __shared__ float lds[FIN_WAVES][64];
-    constexpr int U = 8;
+    constexpr int U = 32;   // a wavefront's run is at most 32 terms on the 64-processor cube: all of them in flight at once
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int r = blockIdx.x;
     const int l = r % g.q, j = (r / g.q) % g.q, i = r / (g.q * g.q);
