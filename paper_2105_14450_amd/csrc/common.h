@@ -79,7 +79,8 @@ __device__ __forceinline__ int64_t axis_offset_fast(const AxisMap &m, int64_t x)
 
 // Element (mn, k) of operand A sits at A[a_mn(mn) + a_k(k)], of B at B[b_mn(mn) + b_k(k)];
 // output element (m, n) at C[c_m(m) + c_n(n)].  bias (optional, fp32) is indexed by bias_n(n)
-// and added to the scaled accumulator before the store.
+// and added to the scaled accumulator before the store (the tuned kernels carry it in the forward
+// product's layout only; a bias with another layout runs on the bounds-checked kernel).
 struct GemmMaps {
     AxisMap a_mn, a_k, b_mn, b_k, c_m, c_n, bias_n;
     const float *bias;

@@ -47,7 +47,8 @@ Plan make_plan(const GemmArgs &g)
         if (!map_ok(m.a_k, g.Kc, align, g.a_kmajor, kpt) || !map_ok(m.b_k, g.Kc, align, g.b_kmajor, kpt)) return p;
         if (!map_ok(m.a_mn, g.Mo, align, !g.a_kmajor, 16) || !map_ok(m.b_mn, g.No, align, !g.b_kmajor, 16)) return p;
         if (!map_ok(m.c_m, g.Mo, oalign, false, 32) || !map_ok(m.c_n, g.No, oalign, true, oalign)) return p;
-        if (m.bias && !map_ok(m.bias_n, g.No, 1, true, 4)) return p;
+        // the bias is the forward product's (the tuned kernels of the other layouts carry none)
+        if (m.bias && (!g.a_kmajor || g.b_kmajor || !map_ok(m.bias_n, g.No, 1, true, 4))) return p;
         if (g.Kc % kpt) return p;                // the K loop takes the four LDS stages per pass
         // the kernel addresses an operand as buffer start + 32-bit byte offset
         if ((axis_offset(m.a_mn, g.Mo - 1) + axis_offset(m.a_k, g.Kc - 1) + 1) * es >= (1ll << 32)) return p;

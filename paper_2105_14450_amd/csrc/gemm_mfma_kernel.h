@@ -267,6 +267,10 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // reads of the previous one are in flight.
     constexpr int ROWB = JH * 32 * ESZ;
     constexpr int NBUF = MAPPED ? 1 : 2;
+    // The optional bias belongs to the forward product (Algorithm 7 follows Algorithm 1): only the
+    // map-addressed kernel of that layout stages and adds it; the launcher sends a bias with any other
+    // layout to the bounds-checked kernel.
+    constexpr bool BIAS = MAPPED && AK && !BKM;
     constexpr int STRIP_BYTES = 32 * ROWB;
     constexpr int EPI_BYTES = NBUF * STRIP_BYTES;
     static_assert(ROWB == 128 || ROWB == 256, "strip rows of 8 or 16 slots");
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     static_assert(LPT % KS == 0, "the loads of a K-tile are dealt out evenly over its k-steps");
     static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024, "LDS budget");
     static_assert(NSTAGE * STAGE_BYTES <= 2 * 65536, "an LDS address is one of two lane registers plus a 16-bit immediate");
-    static_assert(EPI_BASE + WAVES * EPI_BYTES + (MAPPED ? BN * 4 : 0) <= (EPI_SEPARATE ? 160 * 1024 : NSTAGE * STAGE_BYTES),
+    static_assert(EPI_BASE + WAVES * EPI_BYTES + (BIAS ? BN * 4 : 0) <= (EPI_SEPARATE ? 160 * 1024 : NSTAGE * STAGE_BYTES),
                   "epilogue staging (and the bias strip) must fit");
     static_assert((NSTAGE - 2) * LPT <= 63, "vmcnt range");
 
@@ -466,7 +470,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
     // (stage, operand, block, k-step, piece) always fits the 16-bit offset field of the read.
     // (fp8 fragments are twice as large: there the registers are needed for the fragments, and the
     // reads of the upper stages form their address with one add instead.)
-    constexpr bool HI_REGS = E::FI <= 4;
+    // (so do the map-addressed two-stage kernels, which need a few registers for their K walk)
+    constexpr bool HI_REGS = E::FI <= 4 && !(MAPPED && NSTAGE == 2);
     unsigned a_lo[NBA], a_hi[NBA], b_lo[NBB], b_hi[NBB];
 #pragma unroll
     for (int x = 0; x < NBA; ++x) {
@@ -783,11 +788,13 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
         asm volatile("" : "+v"(lane));
         char *epi = smem + EPI_BASE + wave * EPI_BYTES;
         TOut *C;
-        const float *bias_lds = nullptr;     // MAPPED: the bias of this wavefront's first column (zeros without a bias)
+        const float *bias_lds = nullptr;     // BIAS: the bias of this wavefront's first column (zeros without a bias)
         if constexpr (!MAPPED) {
             C = static_cast<TOut *>(p.C) + ebatch * p.sC + esplit * p.sSplit + (em0 + wm * WM) * p.ldc + en0 + wn * WN;
         } else {
             C = static_cast<TOut *>(p.C);
+        }
+        if constexpr (BIAS) {
             // one add per output element whether or not there is a bias: no branch inside the unrolled loops
             float *strip = reinterpret_cast<float *>(smem + EPI_BASE + WAVES * EPI_BYTES);
             __syncthreads();   // the previous item's strip has been read
@@ -813,6 +820,15 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
 #pragma unroll
             for (int jj = 0; jj < JH; ++jj) {
                 const int j = jh * JH + jj;
+                // BIAS: the bias values of a 32-column block are read from LDS in one go, ahead of the
+                // conversions (read where they are used, every group of four columns waits a whole LDS
+                // latency for its own read)
+                f32x4 bv[4];
+                if constexpr (BIAS) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) bv[g] = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     // registers 4g..4g+3 of lane: row lane%32, columns j*32 + 8g + 4*(lane/32) + 0..3
@@ -823,9 +839,8 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma
                     float v0 = acc[i][j][4 * g], v1 = acc[i][j][4 * g + 1];
                     float v2 = acc[i][j][4 * g + 2], v3 = acc[i][j][4 * g + 3];
                     if (scaled) { v0 *= alpha; v1 *= alpha; v2 *= alpha; v3 *= alpha; }
-                    if constexpr (MAPPED) {
-                        const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + j * 32 + 8 * g);
-                        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+                    if constexpr (BIAS) {
+                        v0 += bv[g][0]; v1 += bv[g][1]; v2 += bv[g][2]; v3 += bv[g][3];
                     }
                     if (ESZ == 4) {
                         f32x4 v = {v0, v1, v2, v3};
