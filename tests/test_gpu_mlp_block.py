@@ -53,6 +53,32 @@ def test_activation(kind, zt, ht, n):
         assert np.all(gu.raw_host(h)[n:].view(np.uint8) == 0xFF)
 
 
+@pytest.mark.parametrize("zt", ["f32", "bf16"])
+def test_gelu_far_from_zero_and_at_the_seam(zt):
+    """The device evaluates the normal tail by a polynomial below |z| = 6 and by the Gaussian bound
+    beyond: values at and around the seam, deep in both tails (where the tail underflows) and at the
+    ends of the number range stay finite and within the tolerance of the exact form."""
+    big = 3.0e38 if zt == "f32" else 3.38e38
+    vals = [0.0, 1e-30, 1e-3, 0.5, 2.0, 5.5, 5.99, 6.0, 6.01, 7.0, 8.0, 9.5, 13.0, 27.0, 40.0, 1e4, 1e19, 1e30, big]
+    z64 = np.array([v for x in vals for v in (x, -x)], dtype=np.float64)
+    z_raw, _ = synth.store(z64.astype(np.float32), zt)
+    z = numfmt.decode(z_raw, zt)
+    n = z.size
+    g_raw, _ = synth.store(np.ones(n, dtype=np.float32), "f32")
+    zd, gd = gu.to_device(z_raw), gu.to_device(g_raw)
+    h, dz = gu.empty((n,), "f32"), gu.empty((n,), "f32")
+    c3.cube3d_activation_fwd(KIND["gelu"], gu.CODE[zt], gu.CODE["f32"], zd, h)
+    c3.cube3d_activation_bwd(KIND["gelu"], gu.CODE[zt], gu.CODE["f32"], gu.CODE["f32"], zd, gd, dz)
+    torch.cuda.synchronize()
+    got_h, got_dz = gu.to_host(h, "f32"), gu.to_host(dz, "f32")
+    ref_h, ref_dz = mlp.act(z, "gelu"), mlp.act_grad(z, "gelu")
+    assert np.all(np.isfinite(got_h)) and np.all(np.isfinite(got_dz))
+    assert np.all(np.abs(got_h - ref_h) <= 4e-6 * np.abs(ref_h) + 1e-6)
+    assert np.all(np.abs(got_dz - ref_dz) <= 4e-6 * np.abs(ref_dz) + 1e-6)
+    # deep in the lower tail the result is a (signed) zero or a denormal-sized number, never a large one
+    assert np.all(np.abs(got_h[z < -13.0]) < 1e-30)
+
+
 class Block:
     """Device buffers and descriptors of one MLP block on the q^3 cube (in-place cube products)."""
 
